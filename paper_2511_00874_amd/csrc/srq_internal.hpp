@@ -1,0 +1,56 @@
+// Launchers shared between the translation units of the library (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/srq.h"
+
+namespace srq {
+
+// How a quantize launch stores its codes.
+enum StoreMode {
+  STORE_BYTE = 0,   // one byte per element (INT4 values sign-extended to the byte)
+  STORE_NIBBLE = 1, // INT4 only: two elements per byte along the output's contiguous dim
+  STORE_BF16 = 2    // E4M3 / E5M2 only: the grid value itself as bfloat16 (two bytes per element)
+};
+
+struct QuantArgs {
+  int kind, round, dtype, store;
+  float scale;
+  const float* scale_dev;
+  uint64_t seed, counter_offset;
+};
+
+// codes: rows x cols (transpose_out = 0) or cols x rows (1).  Shapes already validated.
+hipError_t launch_quantize(void* codes, const void* x, size_t rows, size_t cols, int transpose_out,
+                           const QuantArgs& a, hipStream_t stream);
+
+hipError_t launch_absmax_scale(float* scale_out_dev, const void* x, int dtype, size_t n, int kind,
+                               hipStream_t stream);
+
+// out[P][Q] = alpha_scale * sum_r X[p][r] Z[q][r] (+ out if accumulate); alpha_scale =
+// alpha * (*sx_dev or sx) * (*sz_dev or sz), computed on the device in binary32.
+struct GemmScale {
+  float alpha;
+  float sx, sz;
+  const float* sx_dev;
+  const float* sz_dev;
+};
+// Which matrix pipeline multiplies the operands.
+enum Pipe {
+  PIPE_I8 = 0,   // int8 codes, int32 accumulators (exact)
+  PIPE_F8 = 1,   // E4M3 / E5M2 codes on the fp8 pipeline (hardware aligns groups of 8 products)
+  PIPE_BF16 = 2  // E4M3 / E5M2 grid values widened to bfloat16: exact products, binary32 sums
+};
+// R is the contraction length in elements; operand rows hold R bytes (PIPE_I8, PIPE_F8) or
+// 2 R bytes (PIPE_BF16).
+size_t gemm_workspace_bytes(size_t P, size_t Q, size_t R, int pipe);
+hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint8_t* Z, int kindZ,
+                             size_t P, size_t Q, size_t R, int pipe, const GemmScale& s, bool accumulate,
+                             void* workspace, hipStream_t stream);
+
+inline bool kind_is_int(int k) { return k == SRQ_INT8 || k == SRQ_INT4; }
+inline bool kind_is_f8(int k) { return k == SRQ_E4M3 || k == SRQ_E5M2; }
+
+}  // namespace srq

@@ -1,0 +1,327 @@
+// Tensor-level SR quantizer kernels (Def. 3: element-wise, independent thresholds) and the
+// per-tensor absmax scale.  HBM-bound streaming kernels for gfx950: 128-bit loads, one
+// Philox block per 8 consecutive elements, 64-bit (or 32-bit for nibbles) stores.
+#include <type_traits>
+
+#include "srq_device.hpp"
+#include "srq_internal.hpp"
+
+namespace srq {
+namespace {
+
+constexpr int QBLOCK = 256;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Load the 8 elements of group g (element index 8g..8g+7) as binary32; lanes beyond n read 0.
+template <int SRC>
+__device__ __forceinline__ void load_group(float (&v)[8], const void* x, size_t g, size_t n) {
+  const size_t base = g * 8;
+  if (base + 8 <= n) {
+    if constexpr (SRC == SRQ_F32) {
+      const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(x) + base);
+      const f32x4 a = __builtin_nontemporal_load(p);
+      const f32x4 b = __builtin_nontemporal_load(p + 1);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+      v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+      const u32x4 a = __builtin_nontemporal_load(
+          reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(x) + base));
+      v[0] = bf16_to_f32(a.x & 0xFFFFu); v[1] = bf16_to_f32(a.x >> 16);
+      v[2] = bf16_to_f32(a.y & 0xFFFFu); v[3] = bf16_to_f32(a.y >> 16);
+      v[4] = bf16_to_f32(a.z & 0xFFFFu); v[5] = bf16_to_f32(a.z >> 16);
+      v[6] = bf16_to_f32(a.w & 0xFFFFu); v[7] = bf16_to_f32(a.w >> 16);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float e = 0.0f;
+      if (base + j < n) {
+        if constexpr (SRC == SRQ_F32) e = static_cast<const float*>(x)[base + j];
+        else e = bf16_to_f32(static_cast<const uint16_t*>(x)[base + j]);
+      }
+      v[j] = e;
+    }
+  }
+}
+
+// Quantize one group; c[j] = code byte of element j.
+template <int KIND, int ROUND, bool AS_BF16>
+__device__ __forceinline__ void quantize_group(uint32_t (&c)[8], const float (&v)[8], float inv,
+                                               uint64_t block, uint32_t k0, uint32_t k1) {
+  if constexpr (ROUND == SRQ_SR) {
+    uint32_t w[4];
+    philox_block(block, k0, k1, w);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, AS_BF16>(v[j], inv, eps_of(r16_of(w, j)));
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, AS_BF16>(v[j], inv, 0.5f);  // Def. 2
+  }
+}
+
+__device__ __forceinline__ uint32_t pack_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  return a | (b << 8) | (c << 16) | (d << 24);
+}
+__device__ __forceinline__ uint32_t pack_nibbles(const uint32_t (&c)[8]) {
+  uint32_t r = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r |= (c[j] & 0xFu) << (4 * j);
+  return r;
+}
+
+// ---- same-layout output -------------------------------------------------------------------
+template <int KIND, int SRC, int ROUND, int STORE>
+__global__ __launch_bounds__(QBLOCK) void quantize_flat_kernel(uint8_t* __restrict__ out,
+                                                               const void* __restrict__ x, size_t n,
+                                                               float scale, const float* scale_dev,
+                                                               uint64_t seed, uint64_t counter_offset) {
+  const float inv = inv_scale(scale, scale_dev);
+  const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+  const size_t ngroups = (n + 7) / 8;
+  const size_t stride = (size_t)gridDim.x * QBLOCK;
+  for (size_t g = (size_t)blockIdx.x * QBLOCK + threadIdx.x; g < ngroups; g += stride) {
+    float v[8];
+    uint32_t c[8];
+    load_group<SRC>(v, x, g, n);
+    quantize_group<KIND, ROUND, STORE == STORE_BF16>(c, v, inv, counter_offset + g, k0, k1);
+    const size_t base = g * 8;
+    if constexpr (STORE == STORE_NIBBLE) {
+      const uint32_t word = pack_nibbles(c);
+      if (base + 8 <= n) {
+        __builtin_nontemporal_store(word, reinterpret_cast<uint32_t*>(out + base / 2));
+      } else {
+        for (size_t j = 0; base + 2 * j < n; ++j) out[base / 2 + j] = (uint8_t)(word >> (8 * j));
+      }
+    } else if constexpr (STORE == STORE_BF16) {
+      uint16_t* o16 = reinterpret_cast<uint16_t*>(out);
+      if (base + 8 <= n) {
+        u32x4 word = {c[0] | (c[1] << 16), c[2] | (c[3] << 16), c[4] | (c[5] << 16), c[6] | (c[7] << 16)};
+        __builtin_nontemporal_store(word, reinterpret_cast<u32x4*>(o16 + base));
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (base + j < n) o16[base + j] = (uint16_t)c[j];
+      }
+    } else {
+      if (base + 8 <= n) {
+        u32x2 word = {pack_bytes(c[0], c[1], c[2], c[3]), pack_bytes(c[4], c[5], c[6], c[7])};
+        __builtin_nontemporal_store(word, reinterpret_cast<u32x2*>(out + base));
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (base + j < n) out[base + j] = (uint8_t)c[j];
+      }
+    }
+  }
+}
+
+// ---- transposed output --------------------------------------------------------------------
+// A block quantizes a TR x TC tile (thresholds keyed by the row-major SOURCE index, so the
+// codes equal those of the same-layout kernel), turns it through LDS, and writes it as
+// TC rows of TR contiguous codes.
+constexpr int TR = 128, TC = 64;
+
+template <int KIND, int SRC, int ROUND, int STORE>
+__global__ __launch_bounds__(QBLOCK) void quantize_transpose_kernel(
+    uint8_t* __restrict__ out, const void* __restrict__ x, uint32_t rows, uint32_t cols, float scale,
+    const float* scale_dev, uint64_t seed, uint64_t counter_offset) {
+  // one tile element per code: a byte, or 16 bits when the grid values are stored as bfloat16
+  using elem_t = typename std::conditional<STORE == STORE_BF16, uint16_t, uint8_t>::type;
+  constexpr int ES = sizeof(elem_t);
+  constexpr int PITCH = TR + 4 / ES;            // elements; keeps rows 4-byte aligned
+  __shared__ __attribute__((aligned(16))) elem_t tile[TC * PITCH];
+  const float inv = inv_scale(scale, scale_dev);
+  const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+  const uint32_t r0 = blockIdx.y * TR, c0 = blockIdx.x * TC;
+  const size_t n = (size_t)rows * cols;
+#pragma unroll
+  for (int it = 0; it < (TR * TC / 8) / QBLOCK; ++it) {
+    const uint32_t id = it * QBLOCK + threadIdx.x;
+    const uint32_t gc = id % (TC / 8), r = id / (TC / 8);
+    const uint32_t row = r0 + r, col = c0 + gc * 8;
+    uint32_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (row < rows && col < cols) {  // cols % 8 == 0: a group never straddles the edge
+      const size_t g = ((size_t)row * cols + col) / 8;
+      float v[8];
+      load_group<SRC>(v, x, g, n);
+      quantize_group<KIND, ROUND, STORE == STORE_BF16>(c, v, inv, counter_offset + g, k0, k1);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) tile[(gc * 8 + j) * PITCH + r] = (elem_t)c[j];
+  }
+  __syncthreads();
+  // TC columns x (TR / 16) chunks of 16 source rows
+#pragma unroll
+  for (int it = 0; it < (TC * TR / 16) / QBLOCK; ++it) {
+    const uint32_t id = it * QBLOCK + threadIdx.x;
+    const uint32_t ch = id % (TR / 16), c = id / (TR / 16);
+    const uint32_t col = c0 + c, row = r0 + ch * 16;
+    if (col >= cols || row >= rows) continue;
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(&tile[c * PITCH + ch * 16]);
+    uint32_t w[4 * ES];
+#pragma unroll
+    for (int i = 0; i < 4 * ES; ++i) w[i] = src[i];
+    const bool whole = row + 16 <= rows && (rows % 16) == 0;  // 16 rows, aligned destination
+    if constexpr (STORE == STORE_NIBBLE) {
+      // pairs along the output's contiguous dimension (source rows); rows is even
+      auto squeeze = [](uint32_t v) {  // 4 code bytes -> 4 nibbles (16 bits)
+        return (v & 0xFu) | ((v >> 4) & 0xF0u) | ((v >> 8) & 0xF00u) | ((v >> 12) & 0xF000u);
+      };
+      const uint32_t lo = squeeze(w[0]) | (squeeze(w[1]) << 16), hi = squeeze(w[2]) | (squeeze(w[3]) << 16);
+      uint8_t* dst = out + ((size_t)col * rows + row) / 2;
+      if (whole) {
+        *reinterpret_cast<u32x2*>(dst) = u32x2{lo, hi};
+      } else {
+        const uint64_t both = (uint64_t)lo | ((uint64_t)hi << 32);
+        for (uint32_t j = 0; row + 2 * j < rows && j < 8; ++j) dst[j] = (uint8_t)(both >> (8 * j));
+      }
+    } else {
+      elem_t* dst = reinterpret_cast<elem_t*>(out) + (size_t)col * rows + row;
+      if (whole) {
+#pragma unroll
+        for (int i = 0; i < ES; ++i)
+          reinterpret_cast<u32x4*>(dst)[i] = u32x4{w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]};
+      } else {
+        constexpr int PER = 4 / ES;  // elements per 32-bit word
+        for (uint32_t j = 0; j < 16 && row + j < rows; ++j)
+          dst[j] = (elem_t)(w[j / PER] >> (8 * ES * (j % PER)));
+      }
+    }
+  }
+}
+
+// ---- absmax ---------------------------------------------------------------------------------
+// max over the wave of non-negative bit patterns: DPP butterflies inside each row of 16
+// lanes, then the four rows through scalar reads.
+__device__ __forceinline__ uint32_t wave_umax(uint32_t v) {
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true));  // row_half_mirror
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true));  // row_mirror
+  const uint32_t a = __builtin_amdgcn_readlane((int)v, 0), b = __builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t c = __builtin_amdgcn_readlane((int)v, 32), d = __builtin_amdgcn_readlane((int)v, 48);
+  return max(max(a, b), max(c, d));
+}
+
+// |x| as bits, with Inf and NaN ignored (they do not take part in the scale).
+__device__ __forceinline__ uint32_t abs_bits_finite(float f) {
+  const uint32_t a = __float_as_uint(f) & 0x7FFFFFFFu;
+  return a < 0x7F800000u ? a : 0u;
+}
+
+__global__ void absmax_init_kernel(uint32_t* acc) { *acc = 0u; }
+
+template <int SRC>
+__global__ __launch_bounds__(QBLOCK) void absmax_kernel(uint32_t* __restrict__ acc,
+                                                        const void* __restrict__ x, size_t n) {
+  uint32_t m = 0u;
+  const size_t ngroups = (n + 7) / 8;
+  const size_t stride = (size_t)gridDim.x * QBLOCK;
+  for (size_t g = (size_t)blockIdx.x * QBLOCK + threadIdx.x; g < ngroups; g += stride) {
+    float v[8];
+    load_group<SRC>(v, x, g, n);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m = max(m, abs_bits_finite(v[j]));
+  }
+  m = wave_umax(m);
+  __shared__ uint32_t part[QBLOCK / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t b = part[0];
+#pragma unroll
+    for (int i = 1; i < QBLOCK / 64; ++i) b = max(b, part[i]);
+    if (b != 0u) atomicMax(acc, b);  // bit patterns of non-negative floats order like the floats
+  }
+}
+
+__global__ void absmax_finish_kernel(float* scale, float qmax) {
+  const float amax = *scale;  // the accumulator holds the bits of max|x|
+  *scale = amax == 0.0f ? 1.0f : __fdiv_rn(amax, qmax);
+}
+
+int grid_for(size_t work_items, int per_block, int cap) {
+  size_t blocks = (work_items + per_block - 1) / per_block;
+  if (blocks < 1) blocks = 1;
+  if (blocks > (size_t)cap) blocks = cap;
+  return (int)blocks;
+}
+
+float qmax_of(int kind) {
+  switch (kind) {
+    case SRQ_INT8: return 127.0f;
+    case SRQ_INT4: return 7.0f;
+    case SRQ_E4M3: return 448.0f;
+    default: return 57344.0f;
+  }
+}
+
+template <int KIND, int SRC, int ROUND, int STORE>
+hipError_t launch_one(void* codes, const void* x, size_t rows, size_t cols, int transpose_out,
+                      const QuantArgs& a, hipStream_t stream) {
+  if (transpose_out) {
+    dim3 grid((unsigned)((cols + TC - 1) / TC), (unsigned)((rows + TR - 1) / TR));
+    quantize_transpose_kernel<KIND, SRC, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
+        static_cast<uint8_t*>(codes), x, (uint32_t)rows, (uint32_t)cols, a.scale, a.scale_dev, a.seed,
+        a.counter_offset);
+  } else {
+    const size_t n = rows * cols;
+    // a few groups per thread: enough loads in flight per wave, small tail
+    const int grid = grid_for((n + 7) / 8, QBLOCK * 4, 1 << 20);
+    quantize_flat_kernel<KIND, SRC, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
+        static_cast<uint8_t*>(codes), x, n, a.scale, a.scale_dev, a.seed, a.counter_offset);
+  }
+  return hipGetLastError();
+}
+
+template <int KIND, int STORE>
+hipError_t dispatch_src_round(void* codes, const void* x, size_t rows, size_t cols, int tr,
+                              const QuantArgs& a, hipStream_t s) {
+  if (a.dtype == SRQ_F32) {
+    return a.round == SRQ_SR ? launch_one<KIND, SRQ_F32, SRQ_SR, STORE>(codes, x, rows, cols, tr, a, s)
+                             : launch_one<KIND, SRQ_F32, SRQ_RTN, STORE>(codes, x, rows, cols, tr, a, s);
+  }
+  return a.round == SRQ_SR ? launch_one<KIND, SRQ_BF16, SRQ_SR, STORE>(codes, x, rows, cols, tr, a, s)
+                           : launch_one<KIND, SRQ_BF16, SRQ_RTN, STORE>(codes, x, rows, cols, tr, a, s);
+}
+
+}  // namespace
+
+hipError_t launch_quantize(void* codes, const void* x, size_t rows, size_t cols, int transpose_out,
+                           const QuantArgs& a, hipStream_t stream) {
+  if (rows * cols == 0) return hipSuccess;
+  switch (a.kind) {
+    case SRQ_INT8: return dispatch_src_round<SRQ_INT8, STORE_BYTE>(codes, x, rows, cols, transpose_out, a, stream);
+    case SRQ_INT4:
+      return a.store == STORE_NIBBLE
+                 ? dispatch_src_round<SRQ_INT4, STORE_NIBBLE>(codes, x, rows, cols, transpose_out, a, stream)
+                 : dispatch_src_round<SRQ_INT4, STORE_BYTE>(codes, x, rows, cols, transpose_out, a, stream);
+    case SRQ_E4M3:
+      return a.store == STORE_BF16
+                 ? dispatch_src_round<SRQ_E4M3, STORE_BF16>(codes, x, rows, cols, transpose_out, a, stream)
+                 : dispatch_src_round<SRQ_E4M3, STORE_BYTE>(codes, x, rows, cols, transpose_out, a, stream);
+    case SRQ_E5M2:
+      return a.store == STORE_BF16
+                 ? dispatch_src_round<SRQ_E5M2, STORE_BF16>(codes, x, rows, cols, transpose_out, a, stream)
+                 : dispatch_src_round<SRQ_E5M2, STORE_BYTE>(codes, x, rows, cols, transpose_out, a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_absmax_scale(float* scale_out_dev, const void* x, int dtype, size_t n, int kind,
+                               hipStream_t stream) {
+  uint32_t* acc = reinterpret_cast<uint32_t*>(scale_out_dev);
+  absmax_init_kernel<<<1, 1, 0, stream>>>(acc);
+  if (n > 0) {
+    const int grid = grid_for((n + 7) / 8, QBLOCK * 8, 4096);
+    if (dtype == SRQ_F32) absmax_kernel<SRQ_F32><<<grid, QBLOCK, 0, stream>>>(acc, x, n);
+    else absmax_kernel<SRQ_BF16><<<grid, QBLOCK, 0, stream>>>(acc, x, n);
+  }
+  absmax_finish_kernel<<<1, 1, 0, stream>>>(scale_out_dev, qmax_of(kind));
+  return hipGetLastError();
+}
+
+}  // namespace srq

@@ -1,0 +1,201 @@
+"""Thin ctypes binding over libsrq.so: same names as include/srq.h, argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the path runs in the HIP
+kernels.  There is no fallback: if the library is not built this module raises on import.
+"""
+import ctypes as C
+import os
+
+import torch  # first: its HIP runtime must be the one the library binds to
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsrq.so")
+
+OK = 0
+F32, BF16 = 0, 1
+NONE, INT8, INT4, E4M3, E5M2 = 0, 1, 2, 3, 4
+SR, RTN = 0, 1
+OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
+FLAG_F8_PIPELINE = 1
+KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2"}
+QMAX = {INT8: 127.0, INT4: 7.0, E4M3: 448.0, E5M2: 57344.0}
+
+
+class srq_quant(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("round", C.c_int32), ("scale", C.c_float),
+                ("flags", C.c_uint32), ("scale_dev", C.c_void_p), ("seed", C.c_uint64),
+                ("counter_offset", C.c_uint64)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2511_00874_amd.build` "
+        "(there is no CPU fallback)")
+_lib = C.CDLL(LIB_PATH)
+
+_vp, _sz, _qp = C.c_void_p, C.c_size_t, C.POINTER(srq_quant)
+_lib.sr_absmax_scale.argtypes = [_vp, _vp, C.c_int, _sz, C.c_int, _vp]
+_lib.sr_quantize.argtypes = [_vp, _vp, C.c_int, _sz, _sz, C.c_int, _qp, _vp]
+_lib.sr_gemm_codes.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, C.c_float, C.c_float,
+                               _vp, _sz, _vp]
+_lib.sr_gemm_workspace_bytes.argtypes = [_sz, _sz, _sz]
+_lib.sr_gemm_workspace_bytes.restype = _sz
+_lib.sr_linear_fwd.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _vp, _sz, _vp]
+_lib.sr_linear_bwd_data.argtypes = _lib.sr_linear_fwd.argtypes
+_lib.sr_linear_bwd_weight.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp,
+                                      C.c_float, _vp, _sz, _vp]
+_lib.sr_linear_workspace_bytes.argtypes = [C.c_int, _sz, _sz, _sz]
+_lib.sr_linear_workspace_bytes.restype = _sz
+_lib.sr_status_string.argtypes = [C.c_int]
+_lib.sr_status_string.restype = C.c_char_p
+for _n in ("sr_absmax_scale", "sr_quantize", "sr_gemm_codes", "sr_linear_fwd", "sr_linear_bwd_data",
+           "sr_linear_bwd_weight"):
+    getattr(_lib, _n).restype = C.c_int
+
+EXPORTS = ["sr_absmax_scale", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes",
+           "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight",
+           "sr_linear_workspace_bytes", "sr_status_string"]
+
+raw = _lib  # the C entry points themselves, for tests of the error paths
+
+
+class SrqError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        super().__init__(f"srq status {status}: {_lib.sr_status_string(status).decode()}")
+
+
+def _check(status):
+    if status != OK:
+        raise SrqError(status)
+
+
+def status_string(status):
+    return _lib.sr_status_string(status).decode()
+
+
+def _dtype(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("source tensors must be float32 or bfloat16")
+
+
+def _dev(t):
+    if not t.is_cuda:
+        raise RuntimeError("srq needs device tensors: there is no CPU path")
+    if not t.is_contiguous():
+        raise ValueError("tensors must be dense row-major")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Quant:
+    """One quantizer (Delta, eps): format, per-tensor scale (float or 1-element device tensor),
+    rounding mode and position in the Philox stream."""
+
+    def __init__(self, kind, scale, seed=0, counter_offset=0, round_mode=SR, flags=0):
+        self.kind, self.scale, self.seed = kind, scale, seed
+        self.counter_offset, self.round_mode, self.flags = counter_offset, round_mode, flags
+
+    def c(self):
+        q = srq_quant()
+        q.kind, q.round, q.flags = self.kind, self.round_mode, self.flags
+        if isinstance(self.scale, torch.Tensor):
+            q.scale, q.scale_dev = 0.0, _dev(self.scale)
+        else:
+            q.scale, q.scale_dev = float(self.scale), None
+        q.seed = self.seed & (2**64 - 1)
+        q.counter_offset = self.counter_offset & (2**64 - 1)
+        return q
+
+
+def sr_absmax_scale(x, kind, out=None):
+    """Device tensor holding max|x| / Qmax(kind) (1 if x is all zero)."""
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=x.device)
+    _check(_lib.sr_absmax_scale(_dev(out), _dev(x), _dtype(x), x.numel(), kind, _stream()))
+    return out
+
+
+def sr_quantize(x, q, transpose_out=False, out=None):
+    """Codes of x (2-D, or 1-D treated as one row): uint8, packed two per byte for INT4."""
+    rows, cols = (1, x.numel()) if x.dim() == 1 else x.shape
+    n = rows * cols
+    nbytes = n // 2 if q.kind == INT4 else n
+    if out is None:
+        out = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=x.device)[:nbytes]
+    _check(_lib.sr_quantize(_dev(out), _dev(x), _dtype(x), rows, cols, int(bool(transpose_out)),
+                            C.byref(q.c()), _stream()))
+    return out
+
+
+def sr_gemm_workspace_bytes(P, Q, R):
+    return _lib.sr_gemm_workspace_bytes(P, Q, R)
+
+
+def sr_gemm_codes(X, kindX, Z, kindZ, alpha=1.0, out=None, beta=0.0, workspace=None):
+    """out (P,Q) = alpha * X (P,R) . Z (Q,R)^T on codes, one byte per element."""
+    P, R = X.shape
+    Q = Z.shape[0]
+    if out is None:
+        out = torch.empty((P, Q), dtype=torch.float32, device=X.device)
+    need = sr_gemm_workspace_bytes(P, Q, R)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    _check(_lib.sr_gemm_codes(_dev(out), _dev(X), kindX, _dev(Z), kindZ, P, Q, R, alpha, beta,
+                              _dev(workspace) if workspace is not None else None,
+                              workspace.numel() if workspace is not None else 0, _stream()))
+    return out
+
+
+def sr_linear_workspace_bytes(op, M, N, K):
+    return _lib.sr_linear_workspace_bytes(op, M, N, K)
+
+
+def _ws(op, M, N, K, workspace, device):
+    need = sr_linear_workspace_bytes(op, M, N, K)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace
+
+
+def sr_linear_fwd(A, W, qA, qW, out=None, workspace=None):
+    """Alg. 1: Y (M,N) = Q(A) Q(W)^T, A (M,K), W (N,K)."""
+    M, K = A.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    ws = _ws(OP_FWD, M, N, K, workspace, A.device)
+    _check(_lib.sr_linear_fwd(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K,
+                              C.byref(qA.c()), C.byref(qW.c()), _dev(ws), ws.numel(), _stream()))
+    return out
+
+
+def sr_linear_bwd_data(dY, W, qdY, qW, out=None, workspace=None):
+    """Alg. 2: dA (M,K) = Q(dY) Q(W), dY (M,N), W (N,K)."""
+    M, N = dY.shape
+    K = W.shape[1]
+    if out is None:
+        out = torch.empty((M, K), dtype=torch.float32, device=dY.device)
+    ws = _ws(OP_BWD_DATA, M, N, K, workspace, dY.device)
+    _check(_lib.sr_linear_bwd_data(_dev(out), _dev(dY), _dtype(dY), _dev(W), _dtype(W), M, N, K,
+                                   C.byref(qdY.c()), C.byref(qW.c()), _dev(ws), ws.numel(), _stream()))
+    return out
+
+
+def sr_linear_bwd_weight(dY, A, qdY, qA, out=None, beta=0.0, workspace=None):
+    """Alg. 2: dW (N,K) = beta * dW + Q(dY)^T Q(A), dY (M,N), A (M,K)."""
+    M, N = dY.shape
+    K = A.shape[1]
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float32, device=dY.device)
+    ws = _ws(OP_BWD_WEIGHT, M, N, K, workspace, dY.device)
+    _check(_lib.sr_linear_bwd_weight(_dev(out), _dev(dY), _dtype(dY), _dev(A), _dtype(A), M, N, K,
+                                     C.byref(qdY.c()), C.byref(qA.c()), beta, _dev(ws), ws.numel(),
+                                     _stream()))
+    return out

@@ -1,0 +1,175 @@
+"""GPU parity of the code-matrix product and the three linear entry points against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_00874_amd import lib as L
+from paper_2511_00874_amd import synth
+from gpu_util import (DEV, check_product, check_product_f8_pipeline, group_max_sum, host_src, say,
+                      to_dev)
+
+pytestmark = pytest.mark.gpu
+
+PAIRS = [(L.INT8, L.INT8), (L.INT4, L.INT8), (L.E4M3, L.E4M3), (L.E4M3, L.E5M2), (L.E5M2, L.E4M3),
+         (L.E5M2, L.E5M2)]
+
+
+def _rand_codes(shape, kind, seed):
+    rng = np.random.default_rng(seed)
+    if kind == L.INT8:
+        return rng.integers(-127, 128, size=shape).astype(np.int8).view(np.uint8)
+    if kind == L.INT4:
+        return rng.integers(-7, 8, size=shape).astype(np.int8).view(np.uint8)
+    c = rng.integers(0, 256, size=shape).astype(np.uint8)
+    bad = ~np.isfinite(oracle.decode_array(kind, c))   # NaN / Inf codes never come out of the quantizer
+    c[bad] = 0x30
+    return c
+
+
+# shapes chosen to hit: the 64-tile kernel with ragged edges; a contraction that is not a
+# multiple of the 128-byte stage; the 128-tile kernel; the split contraction
+SHAPES = [(64, 128, 128), (70, 90, 48), (33, 1, 16), (200, 136, 272), (1040, 1100, 400), (256, 192, 8192)]
+
+
+@pytest.mark.parametrize("kx,kz", PAIRS)
+@pytest.mark.parametrize("P,Q,R", SHAPES)
+def test_gemm_codes_matches_oracle(kx, kz, P, Q, R):
+    say("gemm", L.KIND_NAMES[kx], L.KIND_NAMES[kz], P, Q, R)
+    X, Z = _rand_codes((P, R), kx, 1), _rand_codes((Q, R), kz, 2)
+    got = L.sr_gemm_codes(to_dev(X), kx, to_dev(Z), kz, alpha=0.25).cpu().numpy()
+    ref, ab = oracle.gemm_fwd(X, kx, 0.5, Z, kz, 0.5, want_abs=True)
+    if kx in (L.INT8, L.INT4):
+        assert np.array_equal(got, ref)     # int32 accumulation is exact, 0.25 scaling too
+    elif P * Q * R <= 200 * 136 * 272:
+        # one-byte float codes run on the fp8 pipeline: hardware-truncated group sums
+        gms = group_max_sum(oracle.decode_array(kx, X), oracle.decode_array(kz, Z), 0.25)
+        check_product_f8_pipeline(got, ref, gms, ab, (kx, kz, P, Q, R))
+    else:
+        assert np.abs(got - ref).max() <= 7 * 2.0**-13 * ab.max()
+
+
+def test_gemm_large_tiles_sampled():
+    # enough tiles for the 256 x 256 kernel; checked on sampled entries
+    P, Q, R = 4096, 3840, 384
+    rng = np.random.default_rng(0)
+    idx = rng.integers(0, P * Q, size=20000).astype(np.uint64)
+    edge = np.array([0, Q - 1, (P - 1) * Q, P * Q - 1, 255 * Q + 255, 256 * Q + 256], dtype=np.uint64)
+    idx = np.concatenate([idx, edge])
+    for kx, kz in ((L.INT8, L.INT8), (L.E5M2, L.E4M3)):
+        say("gemm-large", L.KIND_NAMES[kx], L.KIND_NAMES[kz])
+        X, Z = _rand_codes((P, R), kx, 3), _rand_codes((Q, R), kz, 4)
+        got = L.sr_gemm_codes(to_dev(X), kx, to_dev(Z), kz).cpu().numpy().reshape(-1)[idx.astype(np.int64)]
+        ref, ab = oracle.gemm_fwd(X, kx, 1.0, Z, kz, 1.0, want_abs=True, at=idx)
+        if kx == L.INT8:
+            assert np.array_equal(got, ref)
+        else:
+            assert np.all(np.abs(got - ref) <= 7 * 2.0**-13 * ab)
+
+
+def test_gemm_accumulate_beta_one():
+    P, Q, R = 96, 80, 256
+    X, Z = _rand_codes((P, R), L.INT8, 5), _rand_codes((Q, R), L.INT8, 6)
+    out = torch.full((P, Q), 3.0, device=DEV)
+    L.sr_gemm_codes(to_dev(X), L.INT8, to_dev(Z), L.INT8, out=out, beta=1.0)
+    ref = oracle.gemm_fwd(X, L.INT8, 1.0, Z, L.INT8, 1.0)
+    assert np.array_equal(out.cpu().numpy(), ref + np.float32(3.0))
+
+
+# ---- the linear entry points -----------------------------------------------------------------
+
+def _quants(kinds, tensors, seed, flags=0):
+    """Five quantizers with absmax scales and running block offsets; returns (lib, oracle) pairs."""
+    out, off = {}, 0
+    for name, kind in kinds.items():
+        t = tensors[name.split("_")[0]]
+        scale = oracle.absmax_scale(host_src(t), kind)
+        out[name] = (L.Quant(kind, scale, seed, off, flags=flags), oracle.Quant(kind, scale, seed, off))
+        off += (t.numel() + 7) // 8
+    return out
+
+
+def _layer(M, N, K, seed, std_dy=1.0, w_bf16=False):
+    A, W, dY = synth.single_layer(M, N, K, seed, std_dy=std_dy)
+    return {"A": to_dev(A), "W": to_dev(W, w_bf16), "dY": to_dev(dY)}
+
+
+def _run_layer(t, q, sample=None, beta_check=False, f8_pipeline=False):
+    M, K = t["A"].shape
+    N = t["W"].shape[0]
+    hA, hW, hdY = host_src(t["A"]), host_src(t["W"]), host_src(t["dY"])
+    for name, fn, ofn, args, oargs, size in (
+            ("fwd", L.sr_linear_fwd, oracle.linear_fwd, (t["A"], t["W"], q["A_fwd"][0], q["W_fwd"][0]),
+             (hA, hW, q["A_fwd"][1], q["W_fwd"][1]), M * N),
+            ("bwd_data", L.sr_linear_bwd_data, oracle.linear_bwd_data,
+             (t["dY"], t["W"], q["dY_bwd"][0], q["W_bwd"][0]), (hdY, hW, q["dY_bwd"][1], q["W_bwd"][1]), M * K),
+            ("bwd_weight", L.sr_linear_bwd_weight, oracle.linear_bwd_weight,
+             (t["dY"], t["A"], q["dY_bwd"][0], q["A_bwd"][0]), (hdY, hA, q["dY_bwd"][1], q["A_bwd"][1]), N * K)):
+        say("linear", name, M, N, K)
+        got = fn(*args).cpu().numpy().reshape(-1)
+        if sample is None:
+            ref, ab = ofn(*oargs, want_abs=True)
+        else:
+            idx = np.random.default_rng(1).integers(0, size, size=sample).astype(np.uint64)
+            got = got[idx.astype(np.int64)]
+            ref, ab = ofn(*oargs, want_abs=True, at=idx)
+        if f8_pipeline:
+            # bound of the fp8 pipeline, with sum_g max_g <= sum |x z|
+            ref, ab = ref.reshape(-1).astype(np.float64), ab.reshape(-1).astype(np.float64)
+            assert np.all(np.abs(got - ref) <= (7 * 2.0**-13 + 1e-6) * ab), name
+            rel_rms = np.sqrt(((got - ref) ** 2).mean() / (ref ** 2).mean())
+            say("   fp8 pipeline rms relative error", rel_rms)
+            assert rel_rms < 1e-4
+        else:
+            check_product(got, ref, ab, name)
+    if beta_check:
+        base = L.sr_linear_bwd_weight(t["dY"], t["A"], q["dY_bwd"][0], q["A_bwd"][0])
+        acc = base.clone()
+        L.sr_linear_bwd_weight(t["dY"], t["A"], q["dY_bwd"][0], q["A_bwd"][0], out=acc, beta=1.0)
+        assert torch.equal(acc, base + base)
+
+
+ALL_INT8 = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.INT8, "W_bwd": L.INT8, "dY_bwd": L.INT8}
+
+
+def test_single_layer_int8_all_five_quantizers():
+    # the small CPU-checkable layer: 64 x 128 activations, 128 x 128 weights, seed 0
+    t = _layer(64, 128, 128, 0)
+    _run_layer(t, _quants(ALL_INT8, t, seed=0), beta_check=True)
+
+
+@pytest.mark.parametrize("kinds", [
+    {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.E5M2, "W_bwd": L.E5M2, "dY_bwd": L.E5M2},
+    {"A_fwd": L.E4M3, "W_fwd": L.E4M3, "A_bwd": L.E4M3, "W_bwd": L.E4M3, "dY_bwd": L.E5M2},
+    {"A_fwd": L.INT8, "W_fwd": L.INT4, "A_bwd": L.INT8, "W_bwd": L.INT8, "dY_bwd": L.INT4},
+])
+def test_ragged_layer_mixed_formats(kinds):
+    t = _layer(272, 144, 208, 3, std_dy=1e-3, w_bf16=True)
+    _run_layer(t, _quants(kinds, t, seed=5))
+
+
+def test_gpt2_mlp_shapes_int8_forward_e5m2_backward():
+    # GPT-2-small MLP linears at 8192 tokens; checked on sampled output entries
+    kinds = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.E5M2, "W_bwd": L.E5M2, "dY_bwd": L.E5M2}
+    for name, N, K in synth.GPT2_SMALL_MLP:
+        t = _layer(8192, N, K, 10, std_dy=1e-3)
+        _run_layer(t, _quants(kinds, t, seed=1), sample=65536)
+
+
+def test_llama_shapes_int4_gradient_bf16_weights():
+    # Llama-1B-shaped linears at 4096 tokens: q-projection in full, the MLP ones sampled
+    kinds = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.INT8, "W_bwd": L.INT8, "dY_bwd": L.INT4}
+    t = _layer(4096, 2048, 2048, 20, std_dy=1e-3, w_bf16=True)
+    _run_layer(t, _quants(kinds, t, seed=2))
+    for N, K in ((5632, 2048), (2048, 5632)):
+        t = _layer(4096, N, K, 21, std_dy=1e-3, w_bf16=True)
+        _run_layer(t, _quants(kinds, t, seed=2), sample=65536)
+
+
+def test_fp8_pipeline_flag_same_codes_hardware_rounding():
+    # the fp8 matrix pipeline: same quantized operands, products within the hardware's bound
+    kinds = {"A_fwd": L.E4M3, "W_fwd": L.E4M3, "A_bwd": L.E5M2, "W_bwd": L.E5M2, "dY_bwd": L.E5M2}
+    t = _layer(272, 144, 208, 3, std_dy=1e-3)
+    _run_layer(t, _quants(kinds, t, seed=5, flags=L.FLAG_F8_PIPELINE), f8_pipeline=True)
+    t = _layer(2048, 768, 512, 4, std_dy=1e-3)
+    _run_layer(t, _quants(kinds, t, seed=6, flags=L.FLAG_F8_PIPELINE), sample=20000, f8_pipeline=True)

@@ -1,0 +1,130 @@
+"""GPU parity of sr_quantize / sr_absmax_scale against the CPU oracle: codes bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_00874_amd import lib as L
+from paper_2511_00874_amd import synth
+from gpu_util import DEV, KINDS, host_src, oracle_codes, say, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _specials():
+    tiny = np.float32(1e-40)  # subnormal in binary32
+    v = [0.0, -0.0, np.nan, np.inf, -np.inf, tiny, -tiny, 1e-30, -1e-30, 3e38, -3e38,
+         0.5, -0.5, 1.5, -1.5, 126.5, 127.0, 127.49, -127.5, 448.0, 449.0, 57344.0, 60000.0,
+         2.0**-6, 2.0**-9, 2.0**-10, -(2.0**-10), 2.0**-14, 2.0**-16, 2.0**-17, -(2.0**-17),
+         0.9999999, 1.0000001, 7.0, 7.5, -7.5, 15.99, 16.0, 255.9, 256.0]
+    return np.array(v, dtype=np.float32)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("mode", [L.SR, L.RTN])
+def test_flat_codes_bit_exact_with_ragged_tail(kind, bf16, mode):
+    n = 3 * 256 * 8 * 4 + 2 * 8 + 6      # several blocks, a short last group
+    x = synth.gaussian((n,), 1.0, 7 + kind)
+    x[:_specials().size] = _specials()
+    xd = to_dev(x, bf16)
+    scale = 0.037
+    say("flat", L.KIND_NAMES[kind], "bf16" if bf16 else "f32", mode, n)
+    got = L.sr_quantize(xd, L.Quant(kind, scale, seed=0xDEADBEEFCAFE1234, counter_offset=2**64 - 5,
+                                    round_mode=mode)).cpu().numpy()
+    want = oracle_codes(xd, kind, scale, 0xDEADBEEFCAFE1234, 2**64 - 5, mode)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_scale_one_specials_and_binade_edges(kind):
+    # scale 1: the grid coordinate is the input itself
+    x = np.concatenate([_specials(), -_specials(),
+                        np.float32([oracle.decode(kind, c) for c in range(256)
+                                    if np.isfinite(oracle.decode(kind, c))])])
+    x = np.concatenate([x, np.nextafter(x, np.float32(np.inf)), np.nextafter(x, np.float32(-np.inf))])
+    x = np.resize(x, (x.size + 7) // 8 * 8).astype(np.float32)
+    xd = to_dev(x)
+    for seed in (0, 1, 2):
+        got = L.sr_quantize(xd, L.Quant(kind, 1.0, seed=seed)).cpu().numpy()
+        assert np.array_equal(got, oracle_codes(xd, kind, 1.0, seed, 0)), seed
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("shape", [(128, 64), (130, 72), (300, 200), (2, 8), (1000, 8), (16, 1024)])
+def test_transposed_codes_equal_the_same_codes_transposed(kind, shape):
+    x = synth.gaussian(shape, 2.0, 3)
+    xd = to_dev(x)
+    scale = oracle.absmax_scale(x, kind)
+    say("transpose", L.KIND_NAMES[kind], shape)
+    got = L.sr_quantize(xd, L.Quant(kind, scale, seed=11, counter_offset=77), transpose_out=True).cpu().numpy()
+    want = oracle_codes(xd, kind, scale, 11, 77, transpose=True)
+    assert np.array_equal(got, want)
+    # and the row-major call gives the very same codes (thresholds keyed by source index)
+    got_rm = L.sr_quantize(xd, L.Quant(kind, scale, seed=11, counter_offset=77)).cpu().numpy()
+    assert np.array_equal(got_rm, oracle_codes(xd, kind, scale, 11, 77))
+
+
+def test_bf16_transposed():
+    x = synth.gaussian((256, 136), 0.02, 5)
+    xd = to_dev(x, bf16=True)
+    scale = oracle.absmax_scale(host_src(xd), L.INT8)
+    got = L.sr_quantize(xd, L.Quant(L.INT8, scale, seed=3), transpose_out=True).cpu().numpy()
+    assert np.array_equal(got, oracle_codes(xd, L.INT8, scale, 3, 0, transpose=True))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_absmax_scale_and_device_scale_path(kind, bf16):
+    x = synth.outlier_tensor_np(100003 * 2, 5)
+    x[17] = np.nan
+    x[18] = np.inf
+    xd = to_dev(x, bf16)
+    s_dev = L.sr_absmax_scale(xd, kind)
+    want = oracle.absmax_scale(host_src(xd), kind)
+    assert float(s_dev.item()) == want
+    got = L.sr_quantize(xd, L.Quant(kind, s_dev, seed=9)).cpu().numpy()
+    assert np.array_equal(got, oracle_codes(xd, kind, want, 9, 0))
+    # host scale, same codes
+    got2 = L.sr_quantize(xd, L.Quant(kind, want, seed=9)).cpu().numpy()
+    assert np.array_equal(got, got2)
+
+
+def test_absmax_of_zeros_and_empty():
+    z = torch.zeros(4096, device=DEV)
+    assert float(L.sr_absmax_scale(z, L.INT8).item()) == 1.0
+    e = torch.zeros(0, device=DEV)
+    assert float(L.sr_absmax_scale(e, L.E4M3).item()) == 1.0
+    out = L.sr_quantize(e, L.Quant(L.INT8, 1.0))
+    assert out.numel() == 0
+
+
+def test_statistics_on_gpu_match_the_paper_example():
+    # 0.7 on the integer grid: up with probability 0.7 (worked example after Def. 3)
+    x = torch.full((1 << 20,), 0.7, device=DEV)
+    codes = L.sr_quantize(x, L.Quant(L.INT8, 1.0, seed=123)).cpu().numpy()
+    assert set(np.unique(codes)) == {0, 1}
+    assert abs(codes.mean() - 0.7) < 5 * np.sqrt(0.21 / codes.size)
+    rtn = L.sr_quantize(x, L.Quant(L.INT8, 1.0, round_mode=L.RTN)).cpu().numpy()
+    assert np.all(rtn == 1)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_full_size_standalone_quantize_bit_exact(kind):
+    # the 2^28-element workload of the standalone quantizer, in the launch shape bench.py times
+    n = 1 << 28
+    say("full-size", L.KIND_NAMES[kind], "generate")
+    xd = synth.outlier_tensor_torch(n, 1234, DEV)
+    s_dev = L.sr_absmax_scale(xd, kind)
+    got = L.sr_quantize(xd, L.Quant(kind, s_dev, seed=42, counter_offset=1 << 40))
+    torch.cuda.synchronize()
+    x = xd.cpu().numpy()
+    del xd
+    say("full-size", L.KIND_NAMES[kind], "oracle")
+    scale = oracle.absmax_scale(x, kind)
+    assert float(s_dev.item()) == scale
+    want = oracle.quantize(x, kind, scale, 42, 1 << 40)
+    if kind == L.INT4:
+        want = oracle.pack_int4(want)
+    got = got.cpu().numpy()
+    assert np.array_equal(got, want)
