@@ -94,6 +94,7 @@ int run_linear(float* out, const void* x, int dtx, size_t xr, size_t xc, int x_t
   if (!int_contraction_ok(qx->kind, R)) return SRQ_ERR_UNSUPPORTED;
   const int pipe = pick_pipe(qx, qz);
   if (pipe < 0) return SRQ_ERR_UNSUPPORTED;
+  if (!gemm_operands_addressable(P, Q, R, pipe)) return SRQ_ERR_UNSUPPORTED;
   const int store = pipe == PIPE_BF16 ? STORE_BF16 : STORE_BYTE;
   const LinearLayout l = linear_layout(P, Q, R, pipe);
   if (!workspace || workspace_bytes < l.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
@@ -107,7 +108,8 @@ int run_linear(float* out, const void* x, int dtx, size_t xr, size_t xc, int x_t
   if (launch_quantize(zcodes, z, zr, zc, z_tr, make_args(qz, dtz, store), s) != hipSuccess)
     return SRQ_ERR_HIP;
   GemmScale sc{1.0f, qx->scale, qz->scale, qx->scale_dev, qz->scale_dev};
-  if (launch_gemm_codes(out, xcodes, qx->kind, zcodes, qz->kind, P, Q, R, pipe, sc, beta == 1.0f, gws, s) !=
+  if (launch_gemm_codes(out, xcodes, qx->kind, zcodes, qz->kind, P, Q, R, R * (pipe == PIPE_BF16 ? 2 : 1), pipe, sc,
+                        beta == 1.0f, gws, s) !=
       hipSuccess)
     return SRQ_ERR_HIP;
   return SRQ_OK;
@@ -169,11 +171,12 @@ int sr_gemm_codes(float* out, const void* X, int kindX, const void* Z, int kindZ
   if (st != SRQ_OK) return st;
   if (!int_contraction_ok(kindX, R)) return SRQ_ERR_UNSUPPORTED;
   const int pipe = kind_is_int(kindX) ? PIPE_I8 : PIPE_F8;
+  if (!gemm_operands_addressable(P, Q, R, pipe)) return SRQ_ERR_UNSUPPORTED;
   const size_t need = gemm_workspace_bytes(P, Q, R, pipe);
   if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return SRQ_ERR_WORKSPACE;
   GemmScale sc{alpha, 1.0f, 1.0f, nullptr, nullptr};
   return launch_gemm_codes(out, static_cast<const uint8_t*>(X), kindX, static_cast<const uint8_t*>(Z), kindZ,
-                           P, Q, R, pipe, sc, beta == 1.0f, workspace, static_cast<hipStream_t>(stream)) == hipSuccess
+                           P, Q, R, R, pipe, sc, beta == 1.0f, workspace, static_cast<hipStream_t>(stream)) == hipSuccess
              ? SRQ_OK
              : SRQ_ERR_HIP;
 }

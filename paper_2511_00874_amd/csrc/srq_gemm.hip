@@ -4,15 +4,21 @@
 //   out[p][q] = s * sum_r val(X[p][r]) * val(Z[q][r])        X: P x R, Z: Q x R, R contiguous
 //
 // All three products of Alg. 1 / Alg. 2 have this form once the quantizer has written the
-// codes with the contraction index contiguous.  Integer codes use v_mfma_i32_32x32x32_i8
-// (int32 accumulators, exact), 8-bit float codes use v_mfma_f32_32x32x64_f8f6f4 with the
-// per-operand format select (binary32 accumulators).
+// operands with the contraction index contiguous.  Three matrix pipelines:
+//   int8 codes          v_mfma_i32_32x32x32_i8        int32 accumulators, exact
+//   E4M3/E5M2 as bf16   v_mfma_f32_32x32x16_bf16      exact products, binary32 sums
+//   E4M3/E5M2 codes     v_mfma_f32_32x32x64_f8f6f4    fp8 pipeline (aligns groups of 8 products)
 //
-// Tiling: a workgroup of 4 waves owns a BM x BN output tile; each wave owns a
-// (BM/2) x (BN/2) sub-tile built from 32x32 MFMA tiles.  The contraction runs in steps of
-// BK = 128 bytes: global -> registers (prefetched one step ahead) -> LDS (two buffers, rows of
-// 128 bytes with the 16-byte chunks XOR-swizzled by row so that the MFMA operand reads are
-// bank-conflict free) -> MFMA.
+// Kernel shape.  A workgroup owns a BM x BN output tile, its waves a WGM x WGN grid of
+// sub-tiles made of 32x32 MFMA tiles.  The contraction advances BK = 128 bytes per stage.
+// Operand tiles go from global memory straight into LDS (buffer_load ... lds, 16 bytes per
+// lane, no registers in between) through a ring of STAGES buffers, so the loads of the next
+// stages are in flight while the current one is multiplied; out-of-range rows and the tail of
+// the contraction come back as zeros from the buffer bounds check.  LDS rows are 128 bytes
+// with the 16-byte chunks XOR-swizzled by (row mod 8): the DMA writes 8 full rows per wave
+// instruction and the MFMA operand reads (ds_read_b128, one row per lane) spread over all
+// banks.  The product is computed transposed inside the wave (Z rows as the first MFMA
+// operand) so that each lane ends up with 4 consecutive q of one p: 16-byte output stores.
 #include "srq_internal.hpp"
 
 namespace srq {
@@ -22,10 +28,12 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) void lds_void;
 
-constexpr int BK = 128;       // bytes of contraction per LDS stage
-constexpr int NTHREADS = 256; // 4 waves, 2 x 2
+constexpr int BK = 128;  // bytes of contraction per LDS stage
 
 struct I8Mma {
   using acc_t = v16i;
@@ -55,24 +63,19 @@ struct BF16Mma {
   static __device__ __forceinline__ uint32_t bits(float v) { return __float_as_uint(v); }
 };
 
-// FX / FZ: 0 = E4M3, 1 = E5M2 (the instruction's format selects)
-template <int FX, int FZ>
+// FA / FB: format select of the first / second MFMA operand, 0 = E4M3, 1 = E5M2
+template <int FA, int FB>
 struct F8Mma {
   using acc_t = v16f;
   using frag_t = v8i;
   static constexpr int KSTEP = 64;
   static __device__ __forceinline__ acc_t mma(frag_t a, frag_t b, acc_t c) {
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, FX, FZ, 0, 0, 0, 0);
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, FA, FB, 0, 0, 0, 0);
   }
   static __device__ __forceinline__ float to_f32(float v) { return v; }
   static __device__ __forceinline__ float from_bits(uint32_t b) { return __uint_as_float(b); }
   static __device__ __forceinline__ uint32_t bits(float v) { return __float_as_uint(v); }
 };
-
-// byte offset of 16-byte chunk `chunk` (0..7) of tile row `row` in an LDS stage
-__device__ __forceinline__ uint32_t lds_off(uint32_t row, uint32_t chunk) {
-  return row * BK + ((chunk ^ (row & 7u)) << 4);
-}
 
 struct GemmParams {
   float* out;            // P x Q (final) -- or partial sums when nsplit > 1
@@ -80,8 +83,10 @@ struct GemmParams {
   const uint8_t* X;
   const uint8_t* Z;
   uint32_t P, Q, R;      // R: bytes per operand row (contraction length x element size)
+  uint32_t pitch;        // bytes between operand rows (>= R, multiple of 16)
   uint32_t k_per_split;  // bytes of R per z-slice, multiple of BK
   uint32_t nsplit;
+  uint32_t tiles_p, tiles_q;
   float alpha, sx, sz;
   const float* sx_dev;
   const float* sz_dev;
@@ -94,68 +99,105 @@ __device__ __forceinline__ float total_scale(const GemmParams& g) {
   return __fmul_rn(g.alpha, __fmul_rn(sx, sz));
 }
 
-template <class MMA, int BM, int BN>
-__global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(GemmParams g) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  constexpr int WTM = BM / 2, WTN = BN / 2;  // wave tile
+constexpr uint32_t OOB = 0x80000000u;  // beyond any operand (operands are < 2 GiB): loads as zero
+
+// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, others left at max)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+}
+
+// One wave-level LDS DMA: 64 lanes x 16 bytes from buffer `rsrc` at byte offset `voff` (per
+// lane; out of range reads as zero) to LDS address `lds_addr` + lane * 16.  Written as inline
+// assembly so that the compiler does not serialise the ring of stages behind vmcnt(0): the
+// kernel counts outstanding DMAs itself (wait_vmcnt).
+__device__ __forceinline__ void lds_dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t lds_addr, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(rsrc)
+               : "memory");
+}
+
+template <class MMA, int BM, int BN, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  constexpr int NW = WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile (p x q)
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int STAGE = (BM + BN) * BK;
-  constexpr int XLOADS = BM * (BK / 16) / NTHREADS;  // 16-byte loads per thread per stage
-  constexpr int ZLOADS = BN * (BK / 16) / NTHREADS;
+  constexpr int XL = BM / 8 / NW, ZL = BN / 8 / NW;  // wave-level DMA instructions per stage
+  constexpr int LPW = XL + ZL;
+  static_assert(XL * 8 * NW == BM && ZL * 8 * NW == BN, "tile rows must split over the waves");
+  static_assert((STAGES - 2) * LPW <= 63 && STAGES >= 2, "vmcnt range");
   using acc_t = typename MMA::acc_t;
   using frag_t = typename MMA::frag_t;
-  constexpr int FRAG_CHUNKS = sizeof(frag_t) / 16;  // 16-byte chunks per lane per MFMA
+  constexpr int FC = sizeof(frag_t) / 16;  // 16-byte chunks per lane per MFMA
   constexpr int KSUB = BK / MMA::KSTEP;
 
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-  const uint32_t wm = wave >> 1, wn = wave & 1u;
-  const uint32_t p0 = blockIdx.y * BM, q0 = blockIdx.x * BN;
-  const uint32_t kbeg = blockIdx.z * g.k_per_split;
+  const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);  // the same, known to be uniform
+  const uint32_t wp = wave / WGN, wq = wave % WGN;
+  const uint32_t lds_base = (uint32_t)(size_t)(lds_void*)lds;
+  // tile index: consecutive workgroups walk down a column of tiles, so that the groups
+  // resident together share the same Z tile rows and neighbouring X tile rows in L2
+  const uint32_t bid = blockIdx.x;
+  const uint32_t tq = bid / g.tiles_p, tp = bid % g.tiles_p;
+  const uint32_t p0 = tp * BM, q0 = tq * BN;
+  const uint32_t kbeg = blockIdx.y * g.k_per_split;
   const uint32_t kend = min(g.R, kbeg + g.k_per_split);
   const int ktiles = (int)((kend - kbeg + BK - 1) / BK);
 
-  v4i xreg[XLOADS], zreg[ZLOADS];
+  const __amdgpu_buffer_rsrc_t xrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.X), 0, (int)(g.P * g.pitch), 0x00020000);
+  const __amdgpu_buffer_rsrc_t zrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.Z), 0, (int)(g.Q * g.pitch), 0x00020000);
 
-  auto load_global = [&](int kt) {
-    const uint32_t k0 = kbeg + kt * BK;
+  // LDS layout of a stage: tile row r at r * 128, its logical 16-byte chunk c at physical
+  // chunk c ^ ((r >> 1) & 7).  The LDS has 64 banks (256 bytes per cycle) and serves a
+  // ds_read_b128 sixteen lanes at a time: sixteen consecutive rows reading the same logical
+  // chunk then touch sixteen different 16-byte slots (two rows per 256 bytes, eight swizzle
+  // values per row parity), i.e. no bank conflicts.
+  // DMA addressing: a wave instruction fills 8 tile rows (1 KiB of LDS, lane L at L*16); lane L
+  // fetches row L/8 and the logical chunk whose physical slot is L%8.  (r >> 1) & 7 depends on
+  // the parity of the 8-row block, hence two per-lane offsets.
+  static_assert(XL % 2 == 0 && ZL % 2 == 0, "row blocks of a wave must start at an even block");
+  const uint32_t lrow = lane >> 3;
+  const uint32_t lchunk0 = (lane & 7u) ^ (lane >> 4), lchunk1 = lchunk0 ^ 4u;  // even / odd row block
+  const uint32_t xvoff = (p0 + wave * XL * 8 + lrow) * g.pitch + kbeg;
+  const uint32_t zvoff = (q0 + wave * ZL * 8 + lrow) * g.pitch + kbeg;
+
+  auto issue = [&](int kt, int buf) {
+    const uint32_t koff = (uint32_t)kt * BK;
+    // beyond the contraction the lane loads zeros (offset past the buffer)
+    const uint32_t kc0 = koff + lchunk0 * 16, kc1 = koff + lchunk1 * 16;
+    const bool live0 = kbeg + kc0 < kend, live1 = kbeg + kc1 < kend;
+    const uint32_t xs = lds_base + buf * STAGE + wave_u * XL * 1024;
+    const uint32_t zs = lds_base + buf * STAGE + BM * BK + wave_u * ZL * 1024;
 #pragma unroll
-    for (int i = 0; i < XLOADS; ++i) {
-      const uint32_t id = i * NTHREADS + tid, row = id >> 3, chunk = id & 7u;
-      const uint32_t p = p0 + row, k = k0 + chunk * 16;
-      v4i v = {0, 0, 0, 0};
-      if (p < g.P && k < kend) v = *reinterpret_cast<const v4i*>(g.X + (size_t)p * g.R + k);
-      xreg[i] = v;
-    }
+    for (int i = 0; i < XL; ++i)
+      lds_dma16(xrsrc, xs + i * 1024,
+                (i & 1) ? (live1 ? xvoff + kc1 + i * 8 * g.pitch : OOB) : (live0 ? xvoff + kc0 + i * 8 * g.pitch : OOB));
 #pragma unroll
-    for (int i = 0; i < ZLOADS; ++i) {
-      const uint32_t id = i * NTHREADS + tid, row = id >> 3, chunk = id & 7u;
-      const uint32_t q = q0 + row, k = k0 + chunk * 16;
-      v4i v = {0, 0, 0, 0};
-      if (q < g.Q && k < kend) v = *reinterpret_cast<const v4i*>(g.Z + (size_t)q * g.R + k);
-      zreg[i] = v;
-    }
+    for (int i = 0; i < ZL; ++i)
+      lds_dma16(zrsrc, zs + i * 1024,
+                (i & 1) ? (live1 ? zvoff + kc1 + i * 8 * g.pitch : OOB) : (live0 ? zvoff + kc0 + i * 8 * g.pitch : OOB));
   };
-  auto store_lds = [&](int buf) {
-    uint8_t* xs = lds + buf * STAGE;
-    uint8_t* zs = xs + BM * BK;
+
+  // operand reads: lane (row = lane % 32, kgroup = lane / 32) takes FC chunks per MFMA;
+  // physical chunk = logical ^ ((row >> 1) & 7), and logical = t | kgroup * FC with t a constant
+  const uint32_t swz = ((lane >> 1) & 7u) ^ ((lane >> 5) * FC);
+  uint32_t xoff[KSUB * FC], zoff[KSUB * FC];
 #pragma unroll
-    for (int i = 0; i < XLOADS; ++i) {
-      const uint32_t id = i * NTHREADS + tid;
-      *reinterpret_cast<v4i*>(xs + lds_off(id >> 3, id & 7u)) = xreg[i];
-    }
-#pragma unroll
-    for (int i = 0; i < ZLOADS; ++i) {
-      const uint32_t id = i * NTHREADS + tid;
-      *reinterpret_cast<v4i*>(zs + lds_off(id >> 3, id & 7u)) = zreg[i];
-    }
-  };
-  auto load_frag = [&](const uint8_t* base, uint32_t row, int ks) {
-    // lane (row, kgroup = lane / 32) takes FRAG_CHUNKS consecutive chunks of the row
+  for (int t = 0; t < KSUB * FC; ++t) {
+    const uint32_t tt = (t / FC) * 2 * FC + (t % FC);
+    xoff[t] = (wp * WTM + (lane & 31u)) * BK + ((swz ^ tt) << 4);
+    zoff[t] = BM * BK + (wq * WTN + (lane & 31u)) * BK + ((swz ^ tt) << 4);
+  }
+  auto load_frag = [&](const uint8_t* stage, const uint32_t (&off)[KSUB * FC], int sub, int ks) {
     frag_t f;
-    const uint32_t c0 = ks * (2 * FRAG_CHUNKS) + (lane >> 5) * FRAG_CHUNKS;
 #pragma unroll
-    for (int c = 0; c < FRAG_CHUNKS; ++c) {
-      const v4i part = *reinterpret_cast<const v4i*>(base + lds_off(row, c0 + c));
+    for (int c = 0; c < FC; ++c) {
+      const v4i part = *reinterpret_cast<const v4i*>(stage + off[ks * FC + c] + sub * 32 * BK);
       f[4 * c + 0] = part[0]; f[4 * c + 1] = part[1]; f[4 * c + 2] = part[2]; f[4 * c + 3] = part[3];
     }
     return f;
@@ -169,55 +211,109 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(GemmParams g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-  if (ktiles > 0) {
-    load_global(0);
-    store_lds(0);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < ktiles; ++kt) {
-    const int buf = kt & 1;
-    const bool more = kt + 1 < ktiles;
-    if (more) load_global(kt + 1);
-    const uint8_t* xs = lds + buf * STAGE;
-    const uint8_t* zs = xs + BM * BK;
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s) issue(s, s);  // stages past the end load zeros
+
+  // one stage: the fragments of the sub-steps up to PF ahead are fetched before sub-step ks is
+  // multiplied; the scheduling barriers pin that order (the LDS latency then hides behind the
+  // MFMAs) and bound the number of live fragments (registers)
+  constexpr int PF = KSUB > 2 ? 2 : 1;
+  auto compute = [&](int buf) {
+    const uint8_t* stage = lds + buf * STAGE;
+    frag_t xf[PF + 1][TM], zf[PF + 1][TN];
+    auto fetch = [&](int ks) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) xf[ks % (PF + 1)][i] = load_frag(stage, xoff, i, ks);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) zf[ks % (PF + 1)][j] = load_frag(stage, zoff, j, ks);
+    };
+#pragma unroll
+    for (int ks = 0; ks < PF && ks < KSUB; ++ks) fetch(ks);
 #pragma unroll
     for (int ks = 0; ks < KSUB; ++ks) {
-      frag_t xf[TM], zf[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) xf[i] = load_frag(xs, wm * WTM + i * 32 + (lane & 31u), ks);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) zf[j] = load_frag(zs, wn * WTN + j * 32 + (lane & 31u), ks);
+      if (ks + PF < KSUB) fetch(ks + PF);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = MMA::mma(xf[i], zf[j], acc[i][j]);
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = MMA::mma(zf[ks % (PF + 1)][j], xf[ks % (PF + 1)][i], acc[i][j]);  // MFMA rows: q, columns: p
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (more) store_lds(buf ^ 1);
-    __syncthreads();
+  };
+
+  // ring of STAGES buffers, one barrier per stage: after the barrier of step kt every wave has
+  // finished step kt-1, whose buffer is the one refilled now
+  for (int kt0 = 0; kt0 < ktiles; kt0 += STAGES) {
+#pragma unroll
+    for (int s = 0; s < STAGES; ++s) {
+      const int kt = kt0 + s;
+      if (kt < ktiles) {
+        wait_vmcnt<(STAGES - 2) * LPW>();
+        __syncthreads();
+        issue(kt + STAGES - 1, (s + STAGES - 1) % STAGES);
+        compute(s);
+      }
+    }
   }
 
-  // epilogue: accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, col l%32
+  // epilogue.  MFMA result register r of lane l: MFMA row 8*(r/4) + 4*(l/32) + r%4 (a q),
+  // MFMA column l%32 (a p).  Each wave turns its tile through its own piece of LDS, one band
+  // of 32 p-rows at a time, so that every global store instruction writes whole rows of the
+  // band: WTN * 4 contiguous bytes per row.
+  constexpr int EP_PITCH = WTN + 4;                   // floats; +4 staggers the banks
+  constexpr int EP_WAVE = 32 * EP_PITCH * 4;          // bytes per wave
+  static_assert(NW * EP_WAVE <= STAGES * STAGE, "epilogue staging must fit in the operand ring");
+  constexpr int CPR = WTN / 4;                        // 16-byte chunks per band row
+  constexpr int EP_ITERS = 32 * CPR / 64;
+  wait_vmcnt<0>();   // the zero-filled stages issued past the end must have landed too
+  __syncthreads();
+  uint32_t* ep = reinterpret_cast<uint32_t*>(lds + wave * EP_WAVE);
   const float s = total_scale(g);
+  const bool q_vec = (g.Q & 3u) == 0;
+  const uint32_t qw0 = q0 + wq * WTN;
+  uint32_t* const pbase = g.nsplit > 1 ? g.partial + (size_t)blockIdx.y * g.P * g.Q : nullptr;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const uint32_t q = q0 + wn * WTN + j * 32 + (lane & 31u);
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const uint32_t p = p0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (p < g.P && q < g.Q) {
-          const size_t idx = (size_t)p * g.Q + q;
-          if (g.nsplit > 1) {
-            g.partial[(size_t)blockIdx.z * g.P * g.Q + idx] = MMA::bits(acc[i][j][r]);
-          } else {
-            float v = __fmul_rn(MMA::to_f32(acc[i][j][r]), s);
-            if (g.accumulate) v = __fadd_rn(v, g.out[idx]);
-            g.out[idx] = v;
+      for (int gq = 0; gq < 4; ++gq)
+        *reinterpret_cast<v4u*>(ep + (lane & 31u) * EP_PITCH + j * 32 + 8 * gq + 4 * (lane >> 5)) =
+            v4u{MMA::bits(acc[i][j][4 * gq]), MMA::bits(acc[i][j][4 * gq + 1]), MMA::bits(acc[i][j][4 * gq + 2]),
+                MMA::bits(acc[i][j][4 * gq + 3])};
+    const uint32_t pb = p0 + wp * WTM + i * 32;
+#pragma unroll
+    for (int it = 0; it < EP_ITERS; ++it) {
+      const uint32_t id = it * 64 + lane, row = id / CPR, c = id % CPR;
+      const uint32_t p = pb + row, q = qw0 + c * 4;
+      const v4u raw = *reinterpret_cast<const v4u*>(ep + row * EP_PITCH + c * 4);
+      if (p >= g.P || q >= g.Q) continue;
+      const size_t idx = (size_t)p * g.Q + q;
+      if (pbase) {
+        if (q_vec) {
+          *reinterpret_cast<v4u*>(pbase + idx) = raw;
+        } else {
+          for (int e = 0; e < 4 && q + e < g.Q; ++e) pbase[idx + e] = raw[e];
+        }
+      } else {
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = __fmul_rn(MMA::to_f32(MMA::from_bits(raw[e])), s);
+        float* dst = g.out + idx;
+        if (q_vec) {
+          if (g.accumulate) {
+            const v4f o = *reinterpret_cast<const v4f*>(dst);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = __fadd_rn(v[e], o[e]);
           }
+          *reinterpret_cast<v4f*>(dst) = v4f{v[0], v[1], v[2], v[3]};
+        } else {
+          for (int e = 0; e < 4 && q + e < g.Q; ++e) dst[e] = g.accumulate ? __fadd_rn(v[e], dst[e]) : v[e];
         }
       }
     }
+  }
 }
 
 // Fixed-order sum of the split partials (deterministic), then scale.
@@ -235,23 +331,27 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams g) {
 }
 
 struct Plan {
+  int tile;  // 0: 256x256, 1: 128x128, 2: 64x64
   int bm, bn;
   uint32_t nsplit, k_per_split;
 };
 
 constexpr int NUM_CU = 256;
 
-Plan make_plan(size_t P, size_t Q, size_t R) {
+Plan make_plan(size_t P, size_t Q, size_t row_bytes) {
   Plan pl;
   auto tiles = [&](int bm, int bn) { return ((P + bm - 1) / bm) * ((Q + bn - 1) / bn); };
-  if (tiles(256, 256) >= (size_t)NUM_CU * 3 / 4) { pl.bm = 256; pl.bn = 256; }
-  else if (tiles(128, 128) >= (size_t)NUM_CU / 2) { pl.bm = 128; pl.bn = 128; }
-  else { pl.bm = 64; pl.bn = 64; }
+  // 256 x 256 tiles halve the operand traffic per flop but leave one workgroup per CU; they
+  // pay off once there are several rounds of them.  128 x 128 tiles run two workgroups per
+  // CU, which overlaps one group's output phase with the other's contraction.
+  if (tiles(256, 256) >= (size_t)NUM_CU * 2) { pl.tile = 0; pl.bm = 256; pl.bn = 256; }
+  else if (tiles(128, 128) >= (size_t)NUM_CU / 2) { pl.tile = 1; pl.bm = 128; pl.bn = 128; }
+  else { pl.tile = 2; pl.bm = 64; pl.bn = 64; }
   const size_t t = tiles(pl.bm, pl.bn);
-  const size_t ksteps = (R + BK - 1) / BK;
+  const size_t ksteps = (row_bytes + BK - 1) / BK;
   size_t nsplit = 1;
   if (t < (size_t)NUM_CU && ksteps >= 16) {
-    nsplit = (2 * NUM_CU + t - 1) / t;           // aim at two workgroups per CU
+    nsplit = (NUM_CU + t - 1) / t;               // at least one workgroup per CU
     const size_t max_split = ksteps / 8;         // keep >= 8 stages per slice
     if (nsplit > max_split) nsplit = max_split;
     if (nsplit > 64) nsplit = 64;
@@ -263,18 +363,22 @@ Plan make_plan(size_t P, size_t Q, size_t R) {
   return pl;
 }
 
-template <class MMA, int BM, int BN>
-hipError_t launch_tile(const GemmParams& g, hipStream_t stream) {
-  constexpr int LDS_BYTES = 2 * (BM + BN) * BK;
+template <class MMA, int BM, int BN, int WGM, int WGN, int STAGES>
+hipError_t launch_tile(GemmParams g, hipStream_t stream) {
+  constexpr int LDS_BYTES = STAGES * (BM + BN) * BK;
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+  auto kern = &gemm_nt_kernel<MMA, BM, BN, WGM, WGN, STAGES>;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<MMA, BM, BN>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  dim3 grid((g.Q + BN - 1) / BN, (g.P + BM - 1) / BM, g.nsplit);
-  gemm_nt_kernel<MMA, BM, BN><<<grid, NTHREADS, LDS_BYTES, stream>>>(g);
+  g.tiles_p = (g.P + BM - 1) / BM;
+  g.tiles_q = (g.Q + BN - 1) / BN;
+  dim3 grid(g.tiles_p * g.tiles_q, g.nsplit);
+  kern<<<grid, WGM * WGN * 64, LDS_BYTES, stream>>>(g);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (g.nsplit > 1) {
@@ -289,9 +393,9 @@ hipError_t launch_tile(const GemmParams& g, hipStream_t stream) {
 
 template <class MMA>
 hipError_t launch_mma(const GemmParams& g, const Plan& pl, hipStream_t stream) {
-  if (pl.bm == 256) return launch_tile<MMA, 256, 256>(g, stream);
-  if (pl.bm == 128) return launch_tile<MMA, 128, 128>(g, stream);
-  return launch_tile<MMA, 64, 64>(g, stream);
+  if (pl.tile == 0) return launch_tile<MMA, 256, 256, 2, 4, 2>(g, stream);  // 8 waves of 128 x 64
+  if (pl.tile == 1) return launch_tile<MMA, 128, 128, 2, 2, 2>(g, stream);  // 4 waves of 64 x 64
+  return launch_tile<MMA, 64, 64, 2, 2, 3>(g, stream);
 }
 
 }  // namespace
@@ -301,9 +405,21 @@ size_t gemm_workspace_bytes(size_t P, size_t Q, size_t R, int pipe) {
   return pl.nsplit > 1 ? (size_t)pl.nsplit * P * Q * sizeof(uint32_t) : 0;
 }
 
+size_t gemm_row_pitch(size_t R, int pipe) {
+  const size_t rb = pipe == PIPE_BF16 ? 2 * R : R;
+  // rows whose length is a multiple of 1 KiB would put a whole tile column on a few memory
+  // channels; one extra 128-byte line per row spreads them
+  return rb % 1024 == 0 ? rb + 128 : rb;
+}
+
+bool gemm_operands_addressable(size_t P, size_t Q, size_t R, int pipe) {
+  const size_t rb = gemm_row_pitch(R, pipe);
+  return (P + 256) * rb < (1ull << 31) && (Q + 256) * rb < (1ull << 31);
+}
+
 hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint8_t* Z, int kindZ,
-                             size_t P, size_t Q, size_t R, int pipe, const GemmScale& s, bool accumulate,
-                             void* workspace, hipStream_t stream) {
+                             size_t P, size_t Q, size_t R, size_t pitch, int pipe, const GemmScale& s,
+                             bool accumulate, void* workspace, hipStream_t stream) {
   const size_t row_bytes = pipe == PIPE_BF16 ? 2 * R : R;
   const Plan pl = make_plan(P, Q, row_bytes);
   GemmParams g;
@@ -311,16 +427,19 @@ hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint
   g.partial = static_cast<uint32_t*>(workspace);
   g.X = X; g.Z = Z;
   g.P = (uint32_t)P; g.Q = (uint32_t)Q; g.R = (uint32_t)row_bytes;
+  g.pitch = (uint32_t)pitch;
   g.k_per_split = pl.k_per_split;
   g.nsplit = pl.nsplit;
+  g.tiles_p = g.tiles_q = 0;
   g.alpha = s.alpha; g.sx = s.sx; g.sz = s.sz; g.sx_dev = s.sx_dev; g.sz_dev = s.sz_dev;
   g.accumulate = accumulate ? 1 : 0;
   if (pipe == PIPE_I8) return launch_mma<I8Mma>(g, pl, stream);
   if (pipe == PIPE_BF16) return launch_mma<BF16Mma>(g, pl, stream);
+  // the Z operand is the first MFMA operand, X the second
   const int fx = kindX == SRQ_E5M2, fz = kindZ == SRQ_E5M2;
-  if (!fx && !fz) return launch_mma<F8Mma<0, 0>>(g, pl, stream);
-  if (!fx && fz) return launch_mma<F8Mma<0, 1>>(g, pl, stream);
-  if (fx && !fz) return launch_mma<F8Mma<1, 0>>(g, pl, stream);
+  if (!fz && !fx) return launch_mma<F8Mma<0, 0>>(g, pl, stream);
+  if (!fz && fx) return launch_mma<F8Mma<0, 1>>(g, pl, stream);
+  if (fz && !fx) return launch_mma<F8Mma<1, 0>>(g, pl, stream);
   return launch_mma<F8Mma<1, 1>>(g, pl, stream);
 }
 

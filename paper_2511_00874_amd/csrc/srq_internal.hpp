@@ -46,9 +46,14 @@ enum Pipe {
 // R is the contraction length in elements; operand rows hold R bytes (PIPE_I8, PIPE_F8) or
 // 2 R bytes (PIPE_BF16).
 size_t gemm_workspace_bytes(size_t P, size_t Q, size_t R, int pipe);
+// operand matrices must stay below 2 GiB (32-bit buffer offsets with an out-of-range sentinel)
+bool gemm_operands_addressable(size_t P, size_t Q, size_t R, int pipe);
+// Row pitch (bytes) the linear entry points give the quantized operands of a product.
+size_t gemm_row_pitch(size_t R, int pipe);
+// pitch: bytes between consecutive operand rows (both operands), >= the row length.
 hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint8_t* Z, int kindZ,
-                             size_t P, size_t Q, size_t R, int pipe, const GemmScale& s, bool accumulate,
-                             void* workspace, hipStream_t stream);
+                             size_t P, size_t Q, size_t R, size_t pitch, int pipe, const GemmScale& s,
+                             bool accumulate, void* workspace, hipStream_t stream);
 
 inline bool kind_is_int(int k) { return k == SRQ_INT8 || k == SRQ_INT4; }
 inline bool kind_is_f8(int k) { return k == SRQ_E4M3 || k == SRQ_E5M2; }
