@@ -57,15 +57,17 @@ class Layer:
         self.Y = torch.empty((M, N), dtype=torch.float32, device=dev)
         self.dA = torch.empty((M, K), dtype=torch.float32, device=dev)
         self.dW = torch.empty((N, K), dtype=torch.float32, device=dev)
-        need = max(L.sr_linear_workspace_bytes(op, M, N, K) for op in (L.OP_FWD, L.OP_BWD_DATA, L.OP_BWD_WEIGHT))
+        need = max(L.sr_linear_workspace_bytes(op, M, N, K) for op in (L.OP_FWD, L.OP_BWD))
         self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        self.absmax = L.AbsmaxBatch([(t, kind, s) for t, kind, s in self.src_of.values()])
 
     def step(self, L):
-        for qn, (t, kind, s) in self.src_of.items():
-            L.sr_absmax_scale(t, kind, out=s)
+        # a0: five scales (three passes: A and W feed two formats each); a1-a5: forward, then the
+        # backward pass with one Q(dY) for both products
+        self.absmax.run()
         L.sr_linear_fwd(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], out=self.Y, workspace=self.ws)
-        L.sr_linear_bwd_data(self.dY, self.W, self.q["dY_bwd"], self.q["W_bwd"], out=self.dA, workspace=self.ws)
-        L.sr_linear_bwd_weight(self.dY, self.A, self.q["dY_bwd"], self.q["A_bwd"], out=self.dW, workspace=self.ws)
+        L.sr_linear_bwd(self.dY, self.W, self.A, self.q["dY_bwd"], self.q["W_bwd"], self.q["A_bwd"],
+                        out_dA=self.dA, out_dW=self.dW, workspace=self.ws)
 
     def flops(self):
         return 6.0 * self.M * self.N * self.K

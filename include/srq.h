@@ -94,13 +94,29 @@ typedef struct {
  * rounding).  Integer formats ignore the flag: their products are exact in int32. */
 enum { SRQ_FLAG_F8_PIPELINE = 1 };
 
-enum { SRQ_OP_FWD = 0, SRQ_OP_BWD_DATA = 1, SRQ_OP_BWD_WEIGHT = 2 };
+enum { SRQ_OP_FWD = 0, SRQ_OP_BWD_DATA = 1, SRQ_OP_BWD_WEIGHT = 2, SRQ_OP_BWD = 3 };
 
 /* Per-tensor scale for absmax scaling (a choice of Delta; the paper leaves Delta open):
  * *scale_out_dev = max|x_i| / Qmax(kind) over the finite elements, or 1 if that is zero.
  * x: device, n elements of `dtype`, 16-byte aligned.  n may be 0 (result 1). */
 int sr_absmax_scale(float* scale_out_dev, const void* x, int dtype, size_t n, int kind,
                     void* stream);
+
+/* The same for several tensors at once (at most 8 requests), in two launches however many
+ * there are.  Requests naming the same (x, n, dtype) share one pass over the tensor, so the
+ * scales of A for its forward and backward quantizers cost one read of A.
+ * workspace: device scratch of sr_absmax_workspace_bytes(reqs, count) bytes, 4-byte aligned;
+ * it needs no initialisation.  reqs is host memory, read before the call returns. */
+typedef struct {
+  const void* x;        /* device, 16-byte aligned                  */
+  int32_t dtype;        /* srq_dtype                                */
+  int32_t kind;         /* srq_kind whose Qmax divides the maximum  */
+  size_t n;             /* elements                                 */
+  float* scale_out_dev; /* device, one float                        */
+} srq_absmax_req;
+int sr_absmax_scales(const srq_absmax_req* reqs, int count, void* workspace, size_t workspace_bytes,
+                     void* stream);
+size_t sr_absmax_workspace_bytes(const srq_absmax_req* reqs, int count);
 
 /* Element-wise quantization of a rows x cols tensor (Def. 1-3).
  * codes: device output.  transpose_out = 0: same layout as x (rows x cols); 1: cols x rows.
@@ -144,6 +160,15 @@ int sr_linear_bwd_weight(float* dW, const void* dY, int dtypedY, const void* A, 
                          size_t M, size_t N, size_t K, const srq_quant* qdY_bwd,
                          const srq_quant* qA_bwd, float beta, void* workspace,
                          size_t workspace_bytes, void* stream);
+
+/* The whole backward pass of Alg. 2 in one call: dA and dW as the two entry points above
+ * would give them with the same quantizers, bit for bit, but the output gradient is read and
+ * quantized once and all three operands are quantized in one launch.
+ * workspace: sr_linear_workspace_bytes(SRQ_OP_BWD, M, N, K). */
+int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void* W, int dtypeW,
+                  const void* A, int dtypeA, size_t M, size_t N, size_t K, const srq_quant* qdY_bwd,
+                  const srq_quant* qW_bwd, const srq_quant* qA_bwd, float beta, void* workspace,
+                  size_t workspace_bytes, void* stream);
 
 /* Bytes of device scratch the linear entry points need (quantized operands in the layout
  * the product wants, plus split partial sums), for any format.  op: SRQ_OP_*. */

@@ -57,62 +57,111 @@ int pick_pipe(const srq_quant* qx, const srq_quant* qz) {
 // int32 accumulation is exact while R * 127^2 < 2^31
 bool int_contraction_ok(int kx, size_t R) { return !kind_is_int(kx) || R * 16129ull < (1ull << 31); }
 
-struct LinearLayout {
-  size_t x_bytes, z_bytes, gemm_bytes, total;
-};
-
-// Workspace: [codes of the row operand | codes of the column operand | split partials]
-LinearLayout linear_layout(size_t P, size_t Q, size_t R, int pipe) {
-  LinearLayout l;
-  const size_t es = pipe == PIPE_BF16 ? 2 : 1;
-  l.x_bytes = align_up(P * R * es, WS_ALIGN);
-  l.z_bytes = align_up(Q * R * es, WS_ALIGN);
-  l.gemm_bytes = align_up(gemm_workspace_bytes(P, Q, R, pipe), WS_ALIGN);
-  l.total = l.x_bytes + l.z_bytes + l.gemm_bytes;
-  return l;
+QuantJob make_job(const srq_quant* q, const void* x, int dtype, size_t rows, size_t cols, int transpose,
+                  int store, uint8_t* out, uint8_t* out2) {
+  QuantJob j;
+  j.x = x; j.out = out; j.out2 = out2;
+  j.rows = (uint32_t)rows; j.cols = (uint32_t)cols;
+  j.kind = q->kind; j.round = q->round; j.dtype = dtype; j.store = store; j.transpose = transpose;
+  j.scale = q->scale; j.scale_dev = q->scale_dev;
+  j.seed = q->seed; j.counter_offset = q->counter_offset;
+  j.first_block = j.nblocks = 0;
+  return j;
 }
 
-// One product of Alg. 1 / Alg. 2: quantize both operands into the workspace with the
-// contraction index contiguous, then multiply the codes.
+// Checks shared by the linear entry points for one operand.
+int check_operand(const void* x, int dtype, const srq_quant* q) {
+  if (!x) return SRQ_ERR_NULL;
+  const int st = check_quant(q);
+  if (st != SRQ_OK) return st;
+  if (!dtype_ok(dtype)) return SRQ_ERR_FORMAT;
+  if (!aligned16(x)) return SRQ_ERR_ALIGN;
+  return SRQ_OK;
+}
+
+int check_dims(size_t M, size_t N, size_t K) {
+  if (M == 0 || N == 0 || K == 0) return SRQ_ERR_SHAPE;
+  if (!fits_u32(M) || !fits_u32(N) || !fits_u32(K)) return SRQ_ERR_SHAPE;
+  if ((M % 16) || (N % 16) || (K % 16)) return SRQ_ERR_ALIGN;
+  return SRQ_OK;
+}
+
+// One product out (P x Q) = X (P x R) . Z (Q x R)^T of quantized operands: pipeline, element
+// size and the pieces of workspace it uses.
+struct ProductPlan {
+  int pipe;
+  size_t es, x_bytes, z_bytes, gemm_bytes;
+};
+
+int plan_product(ProductPlan& pp, const srq_quant* qx, const srq_quant* qz, size_t P, size_t Q, size_t R) {
+  int st = check_pair(qx->kind, qz->kind);
+  if (st != SRQ_OK) return st;
+  if (!int_contraction_ok(qx->kind, R)) return SRQ_ERR_UNSUPPORTED;
+  pp.pipe = pick_pipe(qx, qz);
+  if (pp.pipe < 0) return SRQ_ERR_UNSUPPORTED;
+  if (!gemm_operands_addressable(P, Q, R, pp.pipe)) return SRQ_ERR_UNSUPPORTED;
+  pp.es = pp.pipe == PIPE_BF16 ? 2 : 1;
+  pp.x_bytes = align_up(P * R * pp.es, WS_ALIGN);
+  pp.z_bytes = align_up(Q * R * pp.es, WS_ALIGN);
+  pp.gemm_bytes = align_up(gemm_workspace_bytes(P, Q, R, pp.pipe), WS_ALIGN);
+  return SRQ_OK;
+}
+
+// upper bound over the pipelines, for the workspace queries
+size_t product_bytes_max(size_t P, size_t Q, size_t R) {
+  size_t best = 0;
+  for (int pipe : {PIPE_I8, PIPE_BF16}) {
+    const size_t es = pipe == PIPE_BF16 ? 2 : 1;
+    const size_t t = align_up(P * R * es, WS_ALIGN) + align_up(Q * R * es, WS_ALIGN) +
+                     align_up(gemm_workspace_bytes(P, Q, R, pipe), WS_ALIGN);
+    if (t > best) best = t;
+  }
+  return best;
+}
+
+bool workspace_ok(const void* ws, size_t have, size_t need) {
+  return ws && have >= need && (reinterpret_cast<uintptr_t>(ws) & 255u) == 0;
+}
+
+int launch_product(float* out, const uint8_t* xc, const srq_quant* qx, const uint8_t* zc, const srq_quant* qz,
+                   size_t P, size_t Q, size_t R, const ProductPlan& pp, float beta, void* gws, hipStream_t s) {
+  GemmScale sc{1.0f, qx->scale, qz->scale, qx->scale_dev, qz->scale_dev};
+  return launch_gemm_codes(out, xc, qx->kind, zc, qz->kind, P, Q, R, R * pp.es, pp.pipe, sc, beta == 1.0f, gws,
+                           s) == hipSuccess
+             ? SRQ_OK
+             : SRQ_ERR_HIP;
+}
+
+// One product of Alg. 1 / Alg. 2: quantize both operands into the workspace (one launch) with
+// the contraction index contiguous, then multiply.
 //   out (P x Q) = Q(x)[P x R] . Q(z)[Q x R]^T,  x given as xr x xc (transposed if x_tr), same for z
 int run_linear(float* out, const void* x, int dtx, size_t xr, size_t xc, int x_tr, const srq_quant* qx,
                const void* z, int dtz, size_t zr, size_t zc, int z_tr, const srq_quant* qz, size_t P,
                size_t Q, size_t R, float beta, void* workspace, size_t workspace_bytes, void* stream) {
-  if (!out || !x || !z) return SRQ_ERR_NULL;
-  int st = check_quant(qx);
+  if (!out) return SRQ_ERR_NULL;
+  int st = check_operand(x, dtx, qx);
   if (st != SRQ_OK) return st;
-  st = check_quant(qz);
+  st = check_operand(z, dtz, qz);
   if (st != SRQ_OK) return st;
-  if (!dtype_ok(dtx) || !dtype_ok(dtz)) return SRQ_ERR_FORMAT;
-  if (P == 0 || Q == 0 || R == 0) return SRQ_ERR_SHAPE;
-  if (!fits_u32(P) || !fits_u32(Q) || !fits_u32(R)) return SRQ_ERR_SHAPE;
-  if ((P % 16) || (Q % 16) || (R % 16)) return SRQ_ERR_ALIGN;
-  if (!aligned16(out) || !aligned16(x) || !aligned16(z)) return SRQ_ERR_ALIGN;
+  st = check_dims(P, Q, R);
+  if (st != SRQ_OK) return st;
+  if (!aligned16(out)) return SRQ_ERR_ALIGN;
   if (beta != 0.0f && beta != 1.0f) return SRQ_ERR_UNSUPPORTED;
-  st = check_pair(qx->kind, qz->kind);
+  ProductPlan pp;
+  st = plan_product(pp, qx, qz, P, Q, R);
   if (st != SRQ_OK) return st;
-  if (!int_contraction_ok(qx->kind, R)) return SRQ_ERR_UNSUPPORTED;
-  const int pipe = pick_pipe(qx, qz);
-  if (pipe < 0) return SRQ_ERR_UNSUPPORTED;
-  if (!gemm_operands_addressable(P, Q, R, pipe)) return SRQ_ERR_UNSUPPORTED;
-  const int store = pipe == PIPE_BF16 ? STORE_BF16 : STORE_BYTE;
-  const LinearLayout l = linear_layout(P, Q, R, pipe);
-  if (!workspace || workspace_bytes < l.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
-    return SRQ_ERR_WORKSPACE;
+  if (!workspace_ok(workspace, workspace_bytes, pp.x_bytes + pp.z_bytes + pp.gemm_bytes)) return SRQ_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint8_t* xcodes = static_cast<uint8_t*>(workspace);
-  uint8_t* zcodes = xcodes + l.x_bytes;
-  void* gws = zcodes + l.z_bytes;
-  if (launch_quantize(xcodes, x, xr, xc, x_tr, make_args(qx, dtx, store), s) != hipSuccess)
-    return SRQ_ERR_HIP;
-  if (launch_quantize(zcodes, z, zr, zc, z_tr, make_args(qz, dtz, store), s) != hipSuccess)
-    return SRQ_ERR_HIP;
-  GemmScale sc{1.0f, qx->scale, qz->scale, qx->scale_dev, qz->scale_dev};
-  if (launch_gemm_codes(out, xcodes, qx->kind, zcodes, qz->kind, P, Q, R, R * (pipe == PIPE_BF16 ? 2 : 1), pipe, sc,
-                        beta == 1.0f, gws, s) !=
-      hipSuccess)
-    return SRQ_ERR_HIP;
-  return SRQ_OK;
+  uint8_t* zcodes = xcodes + pp.x_bytes;
+  void* gws = zcodes + pp.z_bytes;
+  const int store = pp.pipe == PIPE_BF16 ? STORE_BF16 : STORE_BYTE;
+  QuantJobs jobs;
+  jobs.njobs = 2;
+  jobs.job[0] = make_job(qx, x, dtx, xr, xc, x_tr, store, xcodes, nullptr);
+  jobs.job[1] = make_job(qz, z, dtz, zr, zc, z_tr, store, zcodes, nullptr);
+  if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  return launch_product(out, xcodes, qx, zcodes, qz, P, Q, R, pp, beta, gws, s);
 }
 
 }  // namespace
@@ -126,6 +175,45 @@ int sr_absmax_scale(float* scale_out_dev, const void* x, int dtype, size_t n, in
   return launch_absmax_scale(scale_out_dev, x, dtype, n, kind, static_cast<hipStream_t>(stream)) == hipSuccess
              ? SRQ_OK
              : SRQ_ERR_HIP;
+}
+
+static int build_absmax_batch(AbsmaxBatch& b, const srq_absmax_req* reqs, int count) {
+  if (!reqs) return SRQ_ERR_NULL;
+  if (count < 1 || count > ABSMAX_MAX) return SRQ_ERR_SHAPE;
+  b.ntensors = 0;
+  b.nouts = count;
+  for (int i = 0; i < count; ++i) {
+    const srq_absmax_req& r = reqs[i];
+    if (!r.scale_out_dev || (!r.x && r.n > 0)) return SRQ_ERR_NULL;
+    if (!kind_ok(r.kind) || !dtype_ok(r.dtype)) return SRQ_ERR_FORMAT;
+    if (!aligned16(r.x)) return SRQ_ERR_ALIGN;
+    int t = -1;
+    for (int j = 0; j < b.ntensors; ++j)
+      if (b.x[j] == r.x && b.n[j] == r.n && b.dtype[j] == r.dtype) t = j;
+    if (t < 0) {
+      t = b.ntensors++;
+      b.x[t] = r.x; b.n[t] = r.n; b.dtype[t] = r.dtype;
+    }
+    b.out_tensor[i] = t; b.out_kind[i] = r.kind; b.out[i] = r.scale_out_dev;
+  }
+  return SRQ_OK;
+}
+
+size_t sr_absmax_workspace_bytes(const srq_absmax_req* reqs, int count) {
+  AbsmaxBatch b;
+  if (build_absmax_batch(b, reqs, count) != SRQ_OK) return 0;
+  return absmax_batch_plan(b) * sizeof(uint32_t);
+}
+
+int sr_absmax_scales(const srq_absmax_req* reqs, int count, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  AbsmaxBatch b;
+  const int st = build_absmax_batch(b, reqs, count);
+  if (st != SRQ_OK) return st;
+  const size_t need = absmax_batch_plan(b) * sizeof(uint32_t);
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 3u)) return SRQ_ERR_WORKSPACE;
+  b.partial = static_cast<uint32_t*>(workspace);
+  return launch_absmax_batch(b, static_cast<hipStream_t>(stream)) == hipSuccess ? SRQ_OK : SRQ_ERR_HIP;
 }
 
 int sr_quantize(void* codes, const void* x, int dtype, size_t rows, size_t cols, int transpose_out,
@@ -183,16 +271,13 @@ int sr_gemm_codes(float* out, const void* X, int kindX, const void* Z, int kindZ
 
 size_t sr_linear_workspace_bytes(int op, size_t M, size_t N, size_t K) {
   if (M == 0 || N == 0 || K == 0) return 0;
-  // sized for the widest operand storage (two bytes per element), so that one buffer serves
-  // every format
-  auto widest = [](size_t P, size_t Q, size_t R) {
-    const size_t a = linear_layout(P, Q, R, PIPE_BF16).total, b = linear_layout(P, Q, R, PIPE_I8).total;
-    return a > b ? a : b;
-  };
+  // sized for the widest operand storage (two bytes per element), so one buffer serves every format
   switch (op) {
-    case SRQ_OP_FWD: return widest(M, N, K);         // Y  (M x N), contraction K
-    case SRQ_OP_BWD_DATA: return widest(M, K, N);    // dA (M x K), contraction N
-    case SRQ_OP_BWD_WEIGHT: return widest(N, K, M);  // dW (N x K), contraction M
+    case SRQ_OP_FWD: return product_bytes_max(M, N, K);         // Y  (M x N), contraction K
+    case SRQ_OP_BWD_DATA: return product_bytes_max(M, K, N);    // dA (M x K), contraction N
+    case SRQ_OP_BWD_WEIGHT: return product_bytes_max(N, K, M);  // dW (N x K), contraction M
+    case SRQ_OP_BWD:                                            // both; dY is held in both layouts
+      return product_bytes_max(M, K, N) + product_bytes_max(N, K, M);
     default: return 0;
   }
 }
@@ -219,6 +304,49 @@ int sr_linear_bwd_weight(float* dW, const void* dY, int dtypedY, const void* A, 
                          void* workspace, size_t workspace_bytes, void* stream) {
   return run_linear(dW, dY, dtypedY, M, N, 1, qdY_bwd, A, dtypeA, M, K, 1, qA_bwd, N, K, M, beta,
                     workspace, workspace_bytes, stream);
+}
+
+// Alg. 2 in one call: the output gradient is read and quantized once (one Q(dY), as the
+// algorithm has it) and written in both layouts; W and A are quantized in the same launch.
+int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void* W, int dtypeW, const void* A,
+                  int dtypeA, size_t M, size_t N, size_t K, const srq_quant* qdY_bwd, const srq_quant* qW_bwd,
+                  const srq_quant* qA_bwd, float beta, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dA || !dW) return SRQ_ERR_NULL;
+  int st = check_operand(dY, dtypedY, qdY_bwd);
+  if (st != SRQ_OK) return st;
+  st = check_operand(W, dtypeW, qW_bwd);
+  if (st != SRQ_OK) return st;
+  st = check_operand(A, dtypeA, qA_bwd);
+  if (st != SRQ_OK) return st;
+  st = check_dims(M, N, K);
+  if (st != SRQ_OK) return st;
+  if (!aligned16(dA) || !aligned16(dW)) return SRQ_ERR_ALIGN;
+  if (beta != 0.0f && beta != 1.0f) return SRQ_ERR_UNSUPPORTED;
+  ProductPlan pd, pw;  // dA = dY (M x N) . Wt (K x N)^T ;  dW = dYt (N x M) . At (K x M)^T
+  st = plan_product(pd, qdY_bwd, qW_bwd, M, K, N);
+  if (st != SRQ_OK) return st;
+  st = plan_product(pw, qdY_bwd, qA_bwd, N, K, M);
+  if (st != SRQ_OK) return st;
+  if (pd.pipe != pw.pipe) return SRQ_ERR_UNSUPPORTED;  // one stored form of Q(dY) serves both products
+  const size_t need = pd.x_bytes + pd.z_bytes + pd.gemm_bytes + pw.x_bytes + pw.z_bytes + pw.gemm_bytes;
+  if (!workspace_ok(workspace, workspace_bytes, need)) return SRQ_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint8_t* dy_rm = static_cast<uint8_t*>(workspace);  // M x N
+  uint8_t* w_t = dy_rm + pd.x_bytes;                  // K x N
+  uint8_t* gws_d = w_t + pd.z_bytes;
+  uint8_t* dy_t = gws_d + pd.gemm_bytes;              // N x M
+  uint8_t* a_t = dy_t + pw.x_bytes;                   // K x M
+  uint8_t* gws_w = a_t + pw.z_bytes;
+  const int store = pd.pipe == PIPE_BF16 ? STORE_BF16 : STORE_BYTE;
+  QuantJobs jobs;
+  jobs.njobs = 3;
+  jobs.job[0] = make_job(qdY_bwd, dY, dtypedY, M, N, 1, store, dy_t, dy_rm);
+  jobs.job[1] = make_job(qW_bwd, W, dtypeW, N, K, 1, store, w_t, nullptr);
+  jobs.job[2] = make_job(qA_bwd, A, dtypeA, M, K, 1, store, a_t, nullptr);
+  if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  st = launch_product(dA, dy_rm, qdY_bwd, w_t, qW_bwd, M, K, N, pd, 0.0f, gws_d, s);
+  if (st != SRQ_OK) return st;
+  return launch_product(dW, dy_t, qdY_bwd, a_t, qA_bwd, N, K, M, pw, beta, gws_w, s);
 }
 
 const char* sr_status_string(int status) {

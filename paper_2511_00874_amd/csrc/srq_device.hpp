@@ -105,4 +105,56 @@ __device__ __forceinline__ float inv_scale(float scale, const float* scale_dev) 
   return __fdiv_rn(1.0f, s);
 }
 
+// ---- groups of 8 consecutive elements (one Philox block) -----------------------------------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Load the 8 elements of group g (element index 8g..8g+7) as binary32; lanes beyond n read 0.
+template <int SRC>
+__device__ __forceinline__ void load_group(float (&v)[8], const void* x, size_t g, size_t n) {
+  const size_t base = g * 8;
+  if (base + 8 <= n) {
+    if constexpr (SRC == SRQ_F32) {
+      const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(x) + base);
+      const f32x4 a = __builtin_nontemporal_load(p);
+      const f32x4 b = __builtin_nontemporal_load(p + 1);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+      v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+      const u32x4 a = __builtin_nontemporal_load(
+          reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(x) + base));
+      v[0] = bf16_to_f32(a.x & 0xFFFFu); v[1] = bf16_to_f32(a.x >> 16);
+      v[2] = bf16_to_f32(a.y & 0xFFFFu); v[3] = bf16_to_f32(a.y >> 16);
+      v[4] = bf16_to_f32(a.z & 0xFFFFu); v[5] = bf16_to_f32(a.z >> 16);
+      v[6] = bf16_to_f32(a.w & 0xFFFFu); v[7] = bf16_to_f32(a.w >> 16);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float e = 0.0f;
+      if (base + j < n) {
+        if constexpr (SRC == SRQ_F32) e = static_cast<const float*>(x)[base + j];
+        else e = bf16_to_f32(static_cast<const uint16_t*>(x)[base + j]);
+      }
+      v[j] = e;
+    }
+  }
+}
+
+// Quantize one group; c[j] = code byte of element j.
+template <int KIND, int ROUND, bool AS_BF16>
+__device__ __forceinline__ void quantize_group(uint32_t (&c)[8], const float (&v)[8], float inv,
+                                               uint64_t block, uint32_t k0, uint32_t k1) {
+  if constexpr (ROUND == SRQ_SR) {
+    uint32_t w[4];
+    philox_block(block, k0, k1, w);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, AS_BF16>(v[j], inv, eps_of(r16_of(w, j)));
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, AS_BF16>(v[j], inv, 0.5f);  // Def. 2
+  }
+}
+
 }  // namespace srq

@@ -26,6 +26,43 @@ struct QuantArgs {
 hipError_t launch_quantize(void* codes, const void* x, size_t rows, size_t cols, int transpose_out,
                            const QuantArgs& a, hipStream_t stream);
 
+// Several quantizations in one launch (the operands of a product; in the fused backward pass
+// the output gradient in both layouts).
+constexpr int QUANT_JOBS_MAX = 3;
+struct QuantJob {
+  const void* x;
+  uint8_t* out;    // rows x cols codes, or cols x rows when transpose
+  uint8_t* out2;   // transpose only: optional extra rows x cols copy (same codes), else nullptr
+  uint32_t rows, cols;
+  int kind, round, dtype, store, transpose;
+  float scale;
+  const float* scale_dev;
+  uint64_t seed, counter_offset;
+  uint32_t first_block, nblocks;  // filled by the launcher
+};
+struct QuantJobs {
+  int njobs;
+  QuantJob job[QUANT_JOBS_MAX];
+};
+hipError_t launch_quantize_jobs(QuantJobs& jobs, hipStream_t stream);
+
+// Several per-tensor scales in two launches: up to ABSMAX_MAX distinct tensors and
+// ABSMAX_MAX scales (a tensor may feed several formats).
+constexpr int ABSMAX_MAX = 8;
+struct AbsmaxBatch {
+  int ntensors, nouts;
+  const void* x[ABSMAX_MAX];
+  size_t n[ABSMAX_MAX];
+  int dtype[ABSMAX_MAX];
+  uint32_t first_block[ABSMAX_MAX], nblocks[ABSMAX_MAX];
+  int out_tensor[ABSMAX_MAX], out_kind[ABSMAX_MAX];
+  float out_qmax[ABSMAX_MAX];
+  float* out[ABSMAX_MAX];
+  uint32_t* partial;  // one word per launched block
+};
+size_t absmax_batch_plan(AbsmaxBatch& b);  // fills first_block / nblocks, returns the block count
+hipError_t launch_absmax_batch(AbsmaxBatch& b, hipStream_t stream);
+
 hipError_t launch_absmax_scale(float* scale_out_dev, const void* x, int dtype, size_t n, int kind,
                                hipStream_t stream);
 

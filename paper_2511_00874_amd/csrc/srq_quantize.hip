@@ -11,57 +11,6 @@ namespace {
 
 constexpr int QBLOCK = 256;
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-// Load the 8 elements of group g (element index 8g..8g+7) as binary32; lanes beyond n read 0.
-template <int SRC>
-__device__ __forceinline__ void load_group(float (&v)[8], const void* x, size_t g, size_t n) {
-  const size_t base = g * 8;
-  if (base + 8 <= n) {
-    if constexpr (SRC == SRQ_F32) {
-      const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(x) + base);
-      const f32x4 a = __builtin_nontemporal_load(p);
-      const f32x4 b = __builtin_nontemporal_load(p + 1);
-      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-      v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-    } else {
-      const u32x4 a = __builtin_nontemporal_load(
-          reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(x) + base));
-      v[0] = bf16_to_f32(a.x & 0xFFFFu); v[1] = bf16_to_f32(a.x >> 16);
-      v[2] = bf16_to_f32(a.y & 0xFFFFu); v[3] = bf16_to_f32(a.y >> 16);
-      v[4] = bf16_to_f32(a.z & 0xFFFFu); v[5] = bf16_to_f32(a.z >> 16);
-      v[6] = bf16_to_f32(a.w & 0xFFFFu); v[7] = bf16_to_f32(a.w >> 16);
-    }
-  } else {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      float e = 0.0f;
-      if (base + j < n) {
-        if constexpr (SRC == SRQ_F32) e = static_cast<const float*>(x)[base + j];
-        else e = bf16_to_f32(static_cast<const uint16_t*>(x)[base + j]);
-      }
-      v[j] = e;
-    }
-  }
-}
-
-// Quantize one group; c[j] = code byte of element j.
-template <int KIND, int ROUND, bool AS_BF16>
-__device__ __forceinline__ void quantize_group(uint32_t (&c)[8], const float (&v)[8], float inv,
-                                               uint64_t block, uint32_t k0, uint32_t k1) {
-  if constexpr (ROUND == SRQ_SR) {
-    uint32_t w[4];
-    philox_block(block, k0, k1, w);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, AS_BF16>(v[j], inv, eps_of(r16_of(w, j)));
-  } else {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, AS_BF16>(v[j], inv, 0.5f);  // Def. 2
-  }
-}
-
 __device__ __forceinline__ uint32_t pack_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
   return a | (b << 8) | (c << 16) | (d << 24);
 }
@@ -243,6 +192,61 @@ __global__ void absmax_finish_kernel(float* scale, float qmax) {
   *scale = amax == 0.0f ? 1.0f : __fdiv_rn(amax, qmax);
 }
 
+// ---- several tensors, several scales, two launches -----------------------------------------
+// Launch 1: every block reduces one slice of one tensor and writes its partial maximum to the
+// workspace (plain stores: nothing to initialise).  Launch 2: one block folds the partials of
+// each tensor and writes the requested scales (several formats may share one tensor).
+__global__ __launch_bounds__(QBLOCK) void absmax_multi_kernel(AbsmaxBatch b) {
+  int t = 0;
+#pragma unroll
+  for (int i = 1; i < ABSMAX_MAX; ++i)
+    if (i < b.ntensors && blockIdx.x >= b.first_block[i]) t = i;
+  const uint32_t local = blockIdx.x - b.first_block[t], nblk = b.nblocks[t];
+  const size_t n = b.n[t];
+  const void* x = b.x[t];
+  const size_t ngroups = (n + 7) / 8;
+  uint32_t m = 0u;
+  for (size_t g = (size_t)local * QBLOCK + threadIdx.x; g < ngroups; g += (size_t)nblk * QBLOCK) {
+    float v[8];
+    if (b.dtype[t] == SRQ_F32) load_group<SRQ_F32>(v, x, g, n);
+    else load_group<SRQ_BF16>(v, x, g, n);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m = max(m, abs_bits_finite(v[j]));
+  }
+  m = wave_umax(m);
+  __shared__ uint32_t part[QBLOCK / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t r = part[0];
+#pragma unroll
+    for (int i = 1; i < QBLOCK / 64; ++i) r = max(r, part[i]);
+    b.partial[blockIdx.x] = r;
+  }
+}
+
+__global__ __launch_bounds__(QBLOCK) void absmax_multi_finish_kernel(AbsmaxBatch b) {
+  __shared__ uint32_t part[QBLOCK / 64];
+  __shared__ uint32_t tmax[ABSMAX_MAX];
+  for (int t = 0; t < b.ntensors; ++t) {
+    uint32_t m = 0u;
+    for (uint32_t i = threadIdx.x; i < b.nblocks[t]; i += QBLOCK) m = max(m, b.partial[b.first_block[t] + i]);
+    m = wave_umax(m);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t r = part[0];
+      for (int i = 1; i < QBLOCK / 64; ++i) r = max(r, part[i]);
+      tmax[t] = r;
+    }
+    __syncthreads();
+  }
+  if ((int)threadIdx.x < b.nouts) {
+    const float amax = __uint_as_float(tmax[b.out_tensor[threadIdx.x]]);
+    *b.out[threadIdx.x] = amax == 0.0f ? 1.0f : __fdiv_rn(amax, b.out_qmax[threadIdx.x]);
+  }
+}
+
 int grid_for(size_t work_items, int per_block, int cap) {
   size_t blocks = (work_items + per_block - 1) / per_block;
   if (blocks < 1) blocks = 1;
@@ -309,6 +313,32 @@ hipError_t launch_quantize(void* codes, const void* x, size_t rows, size_t cols,
                  : dispatch_src_round<SRQ_E5M2, STORE_BYTE>(codes, x, rows, cols, transpose_out, a, stream);
     default: return hipErrorInvalidValue;
   }
+}
+
+size_t absmax_batch_plan(AbsmaxBatch& b) {
+  // about eight workgroups per CU in total, shared out by size; at least one per tensor
+  size_t total_groups = 0;
+  for (int t = 0; t < b.ntensors; ++t) total_groups += (b.n[t] + 7) / 8;
+  uint32_t first = 0;
+  for (int t = 0; t < b.ntensors; ++t) {
+    const size_t groups = (b.n[t] + 7) / 8;
+    size_t nb = (groups + QBLOCK * 4 - 1) / (QBLOCK * 4);
+    const size_t share = total_groups ? (2048 * groups + total_groups - 1) / total_groups : 1;
+    if (nb > share) nb = share;
+    if (nb < 1) nb = 1;
+    b.first_block[t] = first;
+    b.nblocks[t] = (uint32_t)nb;
+    first += (uint32_t)nb;
+  }
+  return first;
+}
+
+hipError_t launch_absmax_batch(AbsmaxBatch& b, hipStream_t stream) {
+  const size_t blocks = absmax_batch_plan(b);
+  for (int i = 0; i < b.nouts; ++i) b.out_qmax[i] = qmax_of(b.out_kind[i]);
+  absmax_multi_kernel<<<(unsigned)blocks, QBLOCK, 0, stream>>>(b);
+  absmax_multi_finish_kernel<<<1, QBLOCK, 0, stream>>>(b);
+  return hipGetLastError();
 }
 
 hipError_t launch_absmax_scale(float* scale_out_dev, const void* x, int dtype, size_t n, int kind,

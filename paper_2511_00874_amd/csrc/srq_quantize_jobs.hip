@@ -1,0 +1,156 @@
+// Several tensor quantizations in ONE launch, for the linear entry points: the operands of a
+// product (and, in the fused backward pass, the output gradient in both layouts at once) are
+// independent element-wise jobs (Def. 3), so one grid serves them all and every tensor is
+// read once.  A workgroup first finds its job, then runs the same-layout or the transposing
+// path for that job's format; format, source dtype and rounding mode are uniform per
+// workgroup, so the dispatch is scalar branches.
+#include <type_traits>
+
+#include "srq_device.hpp"
+#include "srq_internal.hpp"
+
+namespace srq {
+namespace {
+
+constexpr int QBLOCK = 256;
+constexpr int TR = 128, TC = 64;        // transposing tile: TR source rows x TC source columns
+constexpr int FLAT_GROUPS_PER_BLOCK = QBLOCK * 4;
+
+template <int KIND, bool AS_BF16>
+__device__ __forceinline__ void job_quantize_group(uint32_t (&c)[8], const float (&v)[8], float inv,
+                                                   const QuantJob& j, uint64_t g, uint32_t k0, uint32_t k1) {
+  if (j.round == SRQ_SR) quantize_group<KIND, SRQ_SR, AS_BF16>(c, v, inv, j.counter_offset + g, k0, k1);
+  else quantize_group<KIND, SRQ_RTN, AS_BF16>(c, v, inv, 0, 0, 0);
+}
+
+__device__ __forceinline__ void job_load_group(float (&v)[8], const QuantJob& j, size_t g, size_t n) {
+  if (j.dtype == SRQ_F32) load_group<SRQ_F32>(v, j.x, g, n);
+  else load_group<SRQ_BF16>(v, j.x, g, n);
+}
+
+// 8 codes of one group to a row-major destination (elements base .. base+7, all in range)
+template <bool AS_BF16>
+__device__ __forceinline__ void store_group(uint8_t* out, size_t base, const uint32_t (&c)[8]) {
+  if constexpr (AS_BF16) {
+    u32x4 w = {c[0] | (c[1] << 16), c[2] | (c[3] << 16), c[4] | (c[5] << 16), c[6] | (c[7] << 16)};
+    *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + base) = w;
+  } else {
+    u32x2 w = {c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24), c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24)};
+    *reinterpret_cast<u32x2*>(out + base) = w;
+  }
+}
+
+// same layout as the source; rows * cols is a multiple of 8 for the linear entry points
+template <int KIND, bool AS_BF16>
+__device__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
+  const float inv = inv_scale(j.scale, j.scale_dev);
+  const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
+  const size_t n = (size_t)j.rows * j.cols, ngroups = n / 8;
+  for (size_t g = (size_t)local * QBLOCK + threadIdx.x; g < ngroups; g += (size_t)nblocks * QBLOCK) {
+    float v[8];
+    uint32_t c[8];
+    job_load_group(v, j, g, n);
+    job_quantize_group<KIND, AS_BF16>(c, v, inv, j, g, k0, k1);
+    store_group<AS_BF16>(j.out, g * 8, c);
+  }
+}
+
+// transposed output (cols x rows), optionally a same-layout copy as well (out2)
+template <int KIND, bool AS_BF16>
+__device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem) {
+  using elem_t = typename std::conditional<AS_BF16, uint16_t, uint8_t>::type;
+  constexpr int ES = sizeof(elem_t);
+  constexpr int PITCH = TR + 4 / ES;
+  elem_t* tile = reinterpret_cast<elem_t*>(smem);
+  const float inv = inv_scale(j.scale, j.scale_dev);
+  const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
+  const uint32_t tiles_x = (j.cols + TC - 1) / TC;
+  const uint32_t r0 = (local / tiles_x) * TR, c0 = (local % tiles_x) * TC;
+  const uint32_t rows = j.rows, cols = j.cols;
+  const size_t n = (size_t)rows * cols;
+#pragma unroll
+  for (int it = 0; it < (TR * TC / 8) / QBLOCK; ++it) {
+    const uint32_t id = it * QBLOCK + threadIdx.x;
+    const uint32_t gc = id % (TC / 8), r = id / (TC / 8);
+    const uint32_t row = r0 + r, col = c0 + gc * 8;
+    uint32_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (row < rows && col < cols) {
+      const size_t g = ((size_t)row * cols + col) / 8;
+      float v[8];
+      job_load_group(v, j, g, n);
+      job_quantize_group<KIND, AS_BF16>(c, v, inv, j, g, k0, k1);
+      if (j.out2) store_group<AS_BF16>(j.out2, g * 8, c);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tile[(gc * 8 + e) * PITCH + r] = (elem_t)c[e];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < (TC * TR / 16) / QBLOCK; ++it) {
+    const uint32_t id = it * QBLOCK + threadIdx.x;
+    const uint32_t ch = id % (TR / 16), c = id / (TR / 16);
+    const uint32_t col = c0 + c, row = r0 + ch * 16;
+    if (col >= cols || row >= rows) continue;  // rows % 16 == 0 for the linear entry points
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(&tile[c * PITCH + ch * 16]);
+    elem_t* dst = reinterpret_cast<elem_t*>(j.out) + (size_t)col * rows + row;
+#pragma unroll
+    for (int i = 0; i < ES; ++i)
+      reinterpret_cast<u32x4*>(dst)[i] = u32x4{src[4 * i], src[4 * i + 1], src[4 * i + 2], src[4 * i + 3]};
+  }
+}
+
+template <int KIND, bool AS_BF16>
+__device__ __forceinline__ void run_job(const QuantJob& j, uint32_t local, uint8_t* smem) {
+  if (j.transpose) transpose_path<KIND, AS_BF16>(j, local, smem);
+  else flat_path<KIND, AS_BF16>(j, local, j.nblocks);
+}
+
+__global__ __launch_bounds__(QBLOCK) void quantize_jobs_kernel(QuantJobs jobs) {
+  __shared__ __attribute__((aligned(16))) uint8_t smem[TC * (TR + 2) * 2];
+  int ji = 0;
+#pragma unroll
+  for (int i = 1; i < QUANT_JOBS_MAX; ++i)
+    if (i < jobs.njobs && blockIdx.x >= jobs.job[i].first_block) ji = i;
+  const QuantJob& j = jobs.job[ji];
+  const uint32_t local = blockIdx.x - j.first_block;
+  const bool bf = j.store == STORE_BF16;
+  switch (j.kind) {
+    case SRQ_INT8: run_job<SRQ_INT8, false>(j, local, smem); break;
+    case SRQ_INT4: run_job<SRQ_INT4, false>(j, local, smem); break;
+    case SRQ_E4M3:
+      if (bf) run_job<SRQ_E4M3, true>(j, local, smem);
+      else run_job<SRQ_E4M3, false>(j, local, smem);
+      break;
+    default:
+      if (bf) run_job<SRQ_E5M2, true>(j, local, smem);
+      else run_job<SRQ_E5M2, false>(j, local, smem);
+      break;
+  }
+}
+
+}  // namespace
+
+// Requirements (checked by the callers): rows % 16 == 0 and cols % 16 == 0 for every job,
+// store is STORE_BYTE or STORE_BF16 (STORE_BF16 only with E4M3 / E5M2).
+hipError_t launch_quantize_jobs(QuantJobs& jobs, hipStream_t stream) {
+  uint32_t first = 0;
+  for (int i = 0; i < jobs.njobs; ++i) {
+    QuantJob& j = jobs.job[i];
+    size_t nb;
+    if (j.transpose) {
+      nb = (size_t)((j.cols + TC - 1) / TC) * ((j.rows + TR - 1) / TR);
+    } else {
+      const size_t groups = (size_t)j.rows * j.cols / 8;
+      nb = (groups + FLAT_GROUPS_PER_BLOCK - 1) / FLAT_GROUPS_PER_BLOCK;
+      if (nb > (1u << 20)) nb = 1u << 20;
+    }
+    j.first_block = first;
+    j.nblocks = (uint32_t)nb;
+    first += (uint32_t)nb;
+  }
+  if (first == 0) return hipSuccess;
+  quantize_jobs_kernel<<<first, QBLOCK, 0, stream>>>(jobs);
+  return hipGetLastError();
+}
+
+}  // namespace srq

@@ -15,7 +15,7 @@ OK = 0
 F32, BF16 = 0, 1
 NONE, INT8, INT4, E4M3, E5M2 = 0, 1, 2, 3, 4
 SR, RTN = 0, 1
-OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
+OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD = 0, 1, 2, 3
 FLAG_F8_PIPELINE = 1
 KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2"}
 QMAX = {INT8: 127.0, INT4: 7.0, E4M3: 448.0, E5M2: 57344.0}
@@ -27,6 +27,11 @@ class srq_quant(C.Structure):
                 ("counter_offset", C.c_uint64)]
 
 
+class srq_absmax_req(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("dtype", C.c_int32), ("kind", C.c_int32), ("n", C.c_size_t),
+                ("scale_out_dev", C.c_void_p)]
+
+
 if not os.path.exists(LIB_PATH):
     raise ImportError(
         f"{LIB_PATH} is missing: build it with `python -m paper_2511_00874_amd.build` "
@@ -35,6 +40,9 @@ _lib = C.CDLL(LIB_PATH)
 
 _vp, _sz, _qp = C.c_void_p, C.c_size_t, C.POINTER(srq_quant)
 _lib.sr_absmax_scale.argtypes = [_vp, _vp, C.c_int, _sz, C.c_int, _vp]
+_lib.sr_absmax_scales.argtypes = [C.POINTER(srq_absmax_req), C.c_int, _vp, _sz, _vp]
+_lib.sr_absmax_workspace_bytes.argtypes = [C.POINTER(srq_absmax_req), C.c_int]
+_lib.sr_absmax_workspace_bytes.restype = _sz
 _lib.sr_quantize.argtypes = [_vp, _vp, C.c_int, _sz, _sz, C.c_int, _qp, _vp]
 _lib.sr_gemm_codes.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, C.c_float, C.c_float,
                                _vp, _sz, _vp]
@@ -44,16 +52,18 @@ _lib.sr_linear_fwd.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _
 _lib.sr_linear_bwd_data.argtypes = _lib.sr_linear_fwd.argtypes
 _lib.sr_linear_bwd_weight.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp,
                                       C.c_float, _vp, _sz, _vp]
+_lib.sr_linear_bwd.argtypes = [_vp, _vp, _vp, C.c_int, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp,
+                               C.c_float, _vp, _sz, _vp]
 _lib.sr_linear_workspace_bytes.argtypes = [C.c_int, _sz, _sz, _sz]
 _lib.sr_linear_workspace_bytes.restype = _sz
 _lib.sr_status_string.argtypes = [C.c_int]
 _lib.sr_status_string.restype = C.c_char_p
-for _n in ("sr_absmax_scale", "sr_quantize", "sr_gemm_codes", "sr_linear_fwd", "sr_linear_bwd_data",
-           "sr_linear_bwd_weight"):
+for _n in ("sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_linear_fwd", "sr_linear_bwd_data",
+           "sr_linear_bwd_weight", "sr_linear_bwd"):
     getattr(_lib, _n).restype = C.c_int
 
-EXPORTS = ["sr_absmax_scale", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes",
-           "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight",
+EXPORTS = ["sr_absmax_scale", "sr_absmax_scales", "sr_absmax_workspace_bytes", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes",
+           "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight", "sr_linear_bwd",
            "sr_linear_workspace_bytes", "sr_status_string"]
 
 raw = _lib  # the C entry points themselves, for tests of the error paths
@@ -120,6 +130,27 @@ def sr_absmax_scale(x, kind, out=None):
         out = torch.empty(1, dtype=torch.float32, device=x.device)
     _check(_lib.sr_absmax_scale(_dev(out), _dev(x), _dtype(x), x.numel(), kind, _stream()))
     return out
+
+
+class AbsmaxBatch:
+    """Prepared sr_absmax_scales call: requests [(tensor, kind, out 1-element tensor)], marshalled once."""
+
+    def __init__(self, requests):
+        self.keep = requests
+        self.count = len(requests)
+        self.reqs = (srq_absmax_req * self.count)()
+        for r, (x, kind, out) in zip(self.reqs, requests):
+            r.x, r.dtype, r.kind, r.n, r.scale_out_dev = _dev(x), _dtype(x), kind, x.numel(), _dev(out)
+        need = _lib.sr_absmax_workspace_bytes(self.reqs, self.count)
+        self.ws = torch.empty(max(need, 4), dtype=torch.uint8, device=requests[0][0].device)
+
+    def run(self):
+        _check(_lib.sr_absmax_scales(self.reqs, self.count, _dev(self.ws), self.ws.numel(), _stream()))
+
+
+def sr_absmax_scales(requests):
+    """requests: [(tensor, kind, out 1-element device tensor)]; all scales in two launches."""
+    AbsmaxBatch(requests).run()
 
 
 def sr_quantize(x, q, transpose_out=False, out=None):
@@ -199,3 +230,18 @@ def sr_linear_bwd_weight(dY, A, qdY, qA, out=None, beta=0.0, workspace=None):
                                      C.byref(qdY.c()), C.byref(qA.c()), beta, _dev(ws), ws.numel(),
                                      _stream()))
     return out
+
+
+def sr_linear_bwd(dY, W, A, qdY, qW, qA, out_dA=None, out_dW=None, beta=0.0, workspace=None):
+    """Alg. 2 in one call: (dA, dW), with dY read and quantized once."""
+    M, N = dY.shape
+    K = W.shape[1]
+    if out_dA is None:
+        out_dA = torch.empty((M, K), dtype=torch.float32, device=dY.device)
+    if out_dW is None:
+        out_dW = torch.empty((N, K), dtype=torch.float32, device=dY.device)
+    ws = _ws(OP_BWD, M, N, K, workspace, dY.device)
+    _check(_lib.sr_linear_bwd(_dev(out_dA), _dev(out_dW), _dev(dY), _dtype(dY), _dev(W), _dtype(W), _dev(A),
+                              _dtype(A), M, N, K, C.byref(qdY.c()), C.byref(qW.c()), C.byref(qA.c()), beta,
+                              _dev(ws), ws.numel(), _stream()))
+    return out_dA, out_dW

@@ -122,6 +122,16 @@ def _run_layer(t, q, sample=None, beta_check=False, f8_pipeline=False):
             assert rel_rms < 1e-4
         else:
             check_product(got, ref, ab, name)
+    # the fused backward pass gives the very same dA and dW (one Q(dY), Alg. 2)
+    fl = 0 if not f8_pipeline else L.FLAG_F8_PIPELINE
+    dA1 = L.sr_linear_bwd_data(t["dY"], t["W"], q["dY_bwd"][0], q["W_bwd"][0])
+    dW1 = L.sr_linear_bwd_weight(t["dY"], t["A"], q["dY_bwd"][0], q["A_bwd"][0])
+    dA2, dW2 = L.sr_linear_bwd(t["dY"], t["W"], t["A"], q["dY_bwd"][0], q["W_bwd"][0], q["A_bwd"][0])
+    assert torch.equal(dA1, dA2) and torch.equal(dW1, dW2), "fused backward differs"
+    if beta_check:
+        acc = dW2.clone()
+        L.sr_linear_bwd(t["dY"], t["W"], t["A"], q["dY_bwd"][0], q["W_bwd"][0], q["A_bwd"][0], out_dW=acc, beta=1.0)
+        assert torch.equal(acc, dW2 + dW2)
     if beta_check:
         base = L.sr_linear_bwd_weight(t["dY"], t["A"], q["dY_bwd"][0], q["A_bwd"][0])
         acc = base.clone()

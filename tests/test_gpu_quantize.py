@@ -90,6 +90,22 @@ def test_absmax_scale_and_device_scale_path(kind, bf16):
     assert np.array_equal(got, got2)
 
 
+def test_batched_absmax_shares_passes_and_matches_oracle():
+    A = to_dev(synth.gaussian((512, 96), 1.0, 1))
+    W = to_dev(synth.gaussian((64, 96), 0.02, 2), bf16=True)
+    dY = to_dev(synth.outlier_tensor_np(512 * 64, 3).reshape(512, 64))
+    Z = torch.zeros(48, device=DEV)
+    outs = torch.empty(6, device=DEV)
+    reqs = [(A, L.INT8, outs[0:1]), (W, L.INT8, outs[1:2]), (A, L.E5M2, outs[2:3]), (W, L.E4M3, outs[3:4]),
+            (dY, L.INT4, outs[4:5]), (Z, L.INT8, outs[5:6])]
+    batch = L.AbsmaxBatch(reqs)
+    for _ in range(2):   # the workspace needs no clearing between calls
+        batch.run()
+        got = outs.cpu().numpy()
+        want = [oracle.absmax_scale(host_src(x), k) for x, k, _ in reqs]
+        assert [float(g) for g in got] == want
+
+
 def test_absmax_of_zeros_and_empty():
     z = torch.zeros(4096, device=DEV)
     assert float(L.sr_absmax_scale(z, L.INT8).item()) == 1.0
