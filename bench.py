@@ -118,41 +118,79 @@ def quantizer_sweep(L, synth, torch, reps):
     return res
 
 
-def gemm_rooflines(L, torch, layers, reps):
-    """The product kernels alone (operands already quantized), by HIP events: per pipeline the
-    average launch duration over the six products of one step and the MFMA rate it reaches."""
+def product_kernel_rooflines(L, torch, layers, reps):
+    """The product kernels alone, operands already quantized, timed by HIP events on the stream
+    they are launched on: the bf16 pipeline (backward products of the default path), the int8
+    pipeline (forward products) and the fp8 pipeline (backward products with the flag set),
+    each over the same shapes the step launches them on."""
+    dev = "cuda:0"
     out = {}
-    for pipe, kind, flag, peak in (("int8", L.INT8, 0, MFMA_PEAK_TFLOPS["int8"]),
-                                   ("fp8", L.E5M2, 1, MFMA_PEAK_TFLOPS["fp8"])):
+
+    def codes(P, R):
+        return torch.randint(0, 120, (P, R), dtype=torch.uint8, device=dev)
+
+    def bf(P, R):
+        return torch.randn((P, R), device=dev).to(torch.bfloat16)
+
+    fwd_shapes = [(ly.M, ly.N, ly.K) for ly in layers]
+    bwd_shapes = [s for ly in layers for s in ((ly.M, ly.K, ly.N), (ly.N, ly.K, ly.M))]
+    for name, shapes, make, call, need_fn, peak, kernel in (
+            ("bf16", bwd_shapes, bf, lambda X, Z, o, ws: L.sr_gemm_bf16(X, Z, out=o, workspace=ws),
+             L.raw.sr_gemm_bf16_workspace_bytes, MFMA_PEAK_TFLOPS["bf16"], "gemm_nt_kernel<BF16Mma, 128, ...>"),
+            ("int8", fwd_shapes, codes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.INT8, Z, L.INT8, out=o, workspace=ws),
+             L.raw.sr_gemm_workspace_bytes, MFMA_PEAK_TFLOPS["int8"], "gemm_nt_kernel<I8Mma, 128, ...>"),
+            ("fp8", bwd_shapes, codes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.E5M2, Z, L.E5M2, out=o, workspace=ws),
+             L.raw.sr_gemm_workspace_bytes, MFMA_PEAK_TFLOPS["fp8"], "gemm_nt_kernel<F8Mma<1,1>, 128, ...>")):
         calls, flops = [], 0.0
-        for ly in layers:
-            for (P, Q, R) in ((ly.M, ly.N, ly.K), (ly.M, ly.K, ly.N), (ly.N, ly.K, ly.M)):
-                X = torch.randint(0, 120, (P, R), dtype=torch.uint8, device="cuda:0")
-                Z = torch.randint(0, 120, (Q, R), dtype=torch.uint8, device="cuda:0")
-                o = torch.empty((P, Q), dtype=torch.float32, device="cuda:0")
-                need = L.sr_gemm_workspace_bytes(P, Q, R)
-                ws = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda:0")
-                calls.append((X, Z, o, ws))
-                flops += 2.0 * P * Q * R
+        for (P, Q, R) in shapes:
+            need = need_fn(P, Q, R)
+            calls.append((make(P, R), make(Q, R), torch.empty((P, Q), dtype=torch.float32, device=dev),
+                          torch.empty(max(need, 16), dtype=torch.uint8, device=dev)))
+            flops += 2.0 * P * Q * R
 
         def run():
             for X, Z, o, ws in calls:
-                L.sr_gemm_codes(X, kind, Z, kind, out=o, workspace=ws)
-        ms = event_ms(torch, run, reps)
-        out[pipe] = {"ms_six_products": round(ms, 4), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 1),
-                     "frac_of_peak": round(flops / (ms * 1e-3) / 1e12 / peak, 4)}
+                call(X, Z, o, ws)
+        ms = event_ms(torch, run, reps) / len(calls)
+        fl = flops / len(calls)
+        tf = fl / (ms * 1e-3) / 1e12
+        out[name] = {"kernel": kernel, "launches": len(calls), "avg_launch_us": round(ms * 1e3, 2),
+                     "flop_per_launch": fl, "TFLOP/s": round(tf, 1), "peak": peak, "frac": round(tf / peak, 4)}
+        del calls
+    torch.cuda.empty_cache()
     return out
 
 
+def phase_times(L, torch, layers, reps):
+    """Entry-point level split of one step, by HIP events."""
+    def absmax():
+        for ly in layers:
+            ly.absmax.run()
+
+    def fwd():
+        for ly in layers:
+            L.sr_linear_fwd(ly.A, ly.W, ly.q["A_fwd"], ly.q["W_fwd"], out=ly.Y, workspace=ly.ws)
+
+    def bwd():
+        for ly in layers:
+            L.sr_linear_bwd(ly.dY, ly.W, ly.A, ly.q["dY_bwd"], ly.q["W_bwd"], ly.q["A_bwd"],
+                            out_dA=ly.dA, out_dW=ly.dW, workspace=ly.ws)
+    res = {n: round(event_ms(torch, f, reps) * 1e3, 1) for n, f in (("absmax_us", absmax), ("fwd_us", fwd), ("bwd_us", bwd))}
+    nbytes = sum(4 * (ly.A.numel() + ly.W.numel() + ly.dY.numel()) for ly in layers)
+    res["absmax_GB/s"] = round(nbytes / (res["absmax_us"] * 1e-6) / 1e9, 1)
+    return res
+
+
 def cpu_baseline(layers_shape):
-    """The CPU oracle on a bounded sample of the same workload: the five quantizations of a
-    512-token slab of fc1 and the three products on sampled output entries."""
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the five absmax
+    scales and five quantizations of fc1 in full (8192 tokens) and the three products on 2^20
+    sampled output entries each."""
     import numpy as np
 
     import oracle
     from paper_2511_00874_amd import synth
     name, N, K = layers_shape[0]
-    M = 512
+    M = TOKENS
     A, W, dY = synth.single_layer(M, N, K, seed=0, std_dy=1e-3)
     t0 = time.perf_counter()
     q = {}
@@ -162,7 +200,7 @@ def cpu_baseline(layers_shape):
         q[qn] = oracle.Quant(kind, oracle.absmax_scale(x, kind), 0, off)
         off += (x.size + 7) // 8
     rng = np.random.default_rng(0)
-    n_out = 1 << 16
+    n_out = 1 << 20
     flops = 0.0
     oracle.linear_fwd(A, W, q["A_fwd"], q["W_fwd"], at=rng.integers(0, M * N, n_out).astype(np.uint64))
     flops += 2.0 * n_out * K
@@ -172,8 +210,9 @@ def cpu_baseline(layers_shape):
     flops += 2.0 * n_out * M
     dt = time.perf_counter() - t0
     return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"fc1 slab of {M} tokens: 5 absmax + 5 quantizations in full, 3 x {n_out} sampled "
-                      f"output entries of Y/dA/dW; {dt:.1f} s of wall time"}
+            "sample": f"fc1 at {M} tokens: 5 absmax + 5 quantizations of the full tensors (each product re-quantizes "
+                      f"its operands, as Alg. 1/2 state), then 3 x {n_out} sampled entries of Y/dA/dW; "
+                      f"{flops / 1e9:.1f} GFLOP of products in {dt:.1f} s wall"}
 
 
 def main():
@@ -191,7 +230,7 @@ def main():
         sys.exit(2)
 
     shapes = synth.GPT2_SMALL_MLP
-    result = {}
+    result, phases, rl = {}, None, None
     for label, flag in (("exact", 0), ("f8_pipeline", L.FLAG_F8_PIPELINE)):
         layers = [Layer(L, synth, torch, nm, TOKENS, N, K, 100 + 10 * i, flag) for i, (nm, N, K) in enumerate(shapes)]
 
@@ -201,14 +240,15 @@ def main():
         sec = time_steps(torch, step, args.steps, args.warmup)
         flops = sum(ly.flops() for ly in layers)
         result[label] = (sec, flops / sec / 1e12)
-        if label == "f8_pipeline":
-            rl = gemm_rooflines(L, torch, layers, max(5, args.steps // 5))
-            # the bf16 pipeline products of the default path, through the linear entry points' own
-            # kernels: time one backward product pair minus nothing -- reported from the profile
+        if label == "exact":
+            reps = max(5, args.steps // 2)
+            phases = phase_times(L, torch, layers, reps)
+            rl = product_kernel_rooflines(L, torch, layers, reps)
         del layers
         torch.cuda.empty_cache()
 
     sec, tflops = result["exact"]
+    io_bytes = sum(4.0 * (3 * TOKENS * K + 3 * N * K + 2 * TOKENS * N) for _, N, K in shapes)
     line = {
         "metric": "SR-quantized linear fwd+bwd TFLOP/s",
         "value": round(tflops, 2),
@@ -220,27 +260,32 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int8 fwd (i32 acc) / e5m2 bwd as bf16 (f32 acc)",
+        "dtype": "int8 (i32 acc) forward; e5m2 values on the bf16 pipeline (f32 acc) backward",
         "data": "synthetic",
         "config": {"workload": "configs[2]: GPT-2-small MLP linears fc1 (3072x768) + fc2 (768x3072), "
-                               "8192 tokens, fp32 in/out, int8 SR forward, E5M2 SR backward, "
-                               "5 absmax + 5 quantizers + 3 products per layer",
-                   "tokens": TOKENS, "flop_per_step": 2 * 6.0 * TOKENS * 768 * 3072},
+                               "8192 tokens, fp32 in/out, int8 SR forward, E5M2 SR backward; per layer "
+                               "5 absmax scales, 5 quantizers, 3 products",
+                   "tokens": TOKENS, "flop_per_step": 2 * 6.0 * TOKENS * 768 * 3072,
+                   "min_hbm_bytes_per_step": io_bytes},
         "frac_of_8bit_mfma_peak": round(tflops / MFMA_PEAK_TFLOPS["int8"], 4),
+        # the path's own ceiling: fp32 tensors in and out once per quantizer pass at HBM peak
+        "composite_ceiling_TFLOP/s": round(2 * 6.0 * TOKENS * 768 * 3072 / (io_bytes / (HBM_PEAK_GBS * 1e9)) / 1e12, 1),
+        "phases": phases,
         "f8_pipeline": {"value": round(result["f8_pipeline"][1], 2), "unit": "TFLOP/s",
                         "ms_per_step": round(result["f8_pipeline"][0] * 1e3, 4),
                         "frac_of_8bit_mfma_peak": round(result["f8_pipeline"][1] / MFMA_PEAK_TFLOPS["fp8"], 4),
-                        "note": "backward products on the fp8 matrix pipeline (hardware-truncated group sums)"},
+                        "note": "backward products on the fp8 matrix pipeline (hardware-truncated group sums, "
+                                "SRQ_FLAG_F8_PIPELINE)"},
         "product_kernels": rl,
     }
-    dom = rl["int8"]
-    line["roofline"] = {"bound": "mfma", "kernel": "gemm_nt_kernel<I8Mma> (six products of one step)",
-                        "achieved": dom["TFLOP/s"], "peak": MFMA_PEAK_TFLOPS["int8"], "unit": "TFLOP/s",
-                        "frac": dom["frac_of_peak"], "traffic": None}
+    dom = rl["bf16"]
+    line["roofline"] = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["TFLOP/s"], "peak": dom["peak"],
+                        "unit": "TFLOP/s", "frac": dom["frac"], "traffic": None,
+                        "note": "dominant kernel of the step by time: 4 of the 6 products; average over its 4 launches"}
     if not args.no_quantizer_sweep:
         qs = quantizer_sweep(L, synth, torch, max(5, args.steps // 5))
         line["sr_quantize"] = qs
-        line["roofline_quantizer"] = {"bound": "hbm", "kernel": "quantize_flat_kernel<INT8,F32,SR> on 2^28 elements",
+        line["roofline_quantizer"] = {"bound": "hbm", "kernel": "quantize_flat_kernel<INT8, F32, SR> on 2^28 elements",
                                       "achieved": qs["int8"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                       "frac": qs["int8"]["frac_of_hbm_peak"], "traffic": None}
     if not args.no_cpu_baseline:

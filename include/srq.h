@@ -141,6 +141,13 @@ int sr_gemm_codes(float* out, const void* X, int kindX, const void* Z, int kindZ
                   size_t workspace_bytes, void* stream);
 size_t sr_gemm_workspace_bytes(size_t P, size_t Q, size_t R);
 
+/* The same product for operands held as bfloat16 values (the form in which the linear entry
+ * points store E4M3 / E5M2 operands by default): X is P x R, Z is Q x R bfloat16, R % 8 == 0.
+ * Products are exact and sums binary32, on the bf16 matrix pipeline. */
+int sr_gemm_bf16(float* out, const void* X, const void* Z, size_t P, size_t Q, size_t R, float alpha,
+                 float beta, void* workspace, size_t workspace_bytes, void* stream);
+size_t sr_gemm_bf16_workspace_bytes(size_t P, size_t Q, size_t R);
+
 /* Forward pass, Alg. 1:  Y = Q(A; qA_fwd) Q(W; qW_fwd)^T.
  * M, N, K multiples of 16.  workspace: sr_linear_workspace_bytes(SRQ_OP_FWD, M, N, K). */
 int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M,

@@ -138,10 +138,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
   const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);  // the same, known to be uniform
   const uint32_t wp = wave / WGN, wq = wave % WGN;
   const uint32_t lds_base = (uint32_t)(size_t)(lds_void*)lds;
-  // tile index: consecutive workgroups walk down a column of tiles, so that the groups
-  // resident together share the same Z tile rows and neighbouring X tile rows in L2
-  const uint32_t bid = blockIdx.x;
-  const uint32_t tq = bid / g.tiles_p, tp = bid % g.tiles_p;
+  // Workgroup -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each
+  // with its own L2.  XCD x takes the contiguous range of tiles [x * chunk, (x+1) * chunk) in
+  // p-major order and walks it with q fastest: the workgroups that share an X row panel run
+  // side by side on one XCD, and an X panel is fetched from memory by one XCD only.
+  const uint32_t ntiles = g.tiles_p * g.tiles_q, chunk = (ntiles + 7u) >> 3;
+  const uint32_t tile = (blockIdx.x & 7u) * chunk + (blockIdx.x >> 3);
+  if (tile >= ntiles) return;  // padding of the last XCD's range (whole workgroup leaves)
+  const uint32_t tp = tile / g.tiles_q, tq = tile % g.tiles_q;
   const uint32_t p0 = tp * BM, q0 = tq * BN;
   const uint32_t kbeg = blockIdx.y * g.k_per_split;
   const uint32_t kend = min(g.R, kbeg + g.k_per_split);
@@ -331,7 +335,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams g) {
 }
 
 struct Plan {
-  int tile;  // 0: 256x256, 1: 128x128, 2: 64x64
+  int tile;  // 0: 256x256, 1: 128x128, 2: 64x64, 3: 128x192
   int bm, bn;
   uint32_t nsplit, k_per_split;
 };
@@ -342,10 +346,16 @@ Plan make_plan(size_t P, size_t Q, size_t row_bytes) {
   Plan pl;
   auto tiles = [&](int bm, int bn) { return ((P + bm - 1) / bm) * ((Q + bn - 1) / bn); };
   // 256 x 256 tiles halve the operand traffic per flop but leave one workgroup per CU; they
-  // pay off once there are several rounds of them.  128 x 128 tiles run two workgroups per
-  // CU, which overlaps one group's output phase with the other's contraction.
+  // pay off once there are several rounds of them.  The 128-row tiles run two workgroups per
+  // CU, which overlaps one group's output phase with the other's contraction; between
+  // 128 x 128 and 128 x 192 the one with fewer rounds of work over the CUs wins (8192 x 768
+  // is 384 tiles of the first, one and a half per CU, but exactly 256 of the second).
+  auto rounds_cost = [&](int bm, int bn) { return ((tiles(bm, bn) + NUM_CU - 1) / NUM_CU) * (size_t)bm * bn; };
   if (tiles(256, 256) >= (size_t)NUM_CU * 2) { pl.tile = 0; pl.bm = 256; pl.bn = 256; }
-  else if (tiles(128, 128) >= (size_t)NUM_CU / 2) { pl.tile = 1; pl.bm = 128; pl.bn = 128; }
+  else if (tiles(128, 128) >= (size_t)NUM_CU / 2) {
+    if (rounds_cost(128, 192) < rounds_cost(128, 128)) { pl.tile = 3; pl.bm = 128; pl.bn = 192; }
+    else { pl.tile = 1; pl.bm = 128; pl.bn = 128; }
+  }
   else { pl.tile = 2; pl.bm = 64; pl.bn = 64; }
   const size_t t = tiles(pl.bm, pl.bn);
   const size_t ksteps = (row_bytes + BK - 1) / BK;
@@ -377,7 +387,7 @@ hipError_t launch_tile(GemmParams g, hipStream_t stream) {
   }
   g.tiles_p = (g.P + BM - 1) / BM;
   g.tiles_q = (g.Q + BN - 1) / BN;
-  dim3 grid(g.tiles_p * g.tiles_q, g.nsplit);
+  dim3 grid(((g.tiles_p * g.tiles_q + 7) / 8) * 8, g.nsplit);
   kern<<<grid, WGM * WGN * 64, LDS_BYTES, stream>>>(g);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -395,6 +405,7 @@ template <class MMA>
 hipError_t launch_mma(const GemmParams& g, const Plan& pl, hipStream_t stream) {
   if (pl.tile == 0) return launch_tile<MMA, 256, 256, 2, 4, 2>(g, stream);  // 8 waves of 128 x 64
   if (pl.tile == 1) return launch_tile<MMA, 128, 128, 2, 2, 2>(g, stream);  // 4 waves of 64 x 64
+  if (pl.tile == 3) return launch_tile<MMA, 128, 192, 2, 2, 2>(g, stream);  // 4 waves of 64 x 96
   return launch_tile<MMA, 64, 64, 2, 2, 3>(g, stream);
 }
 
@@ -405,15 +416,8 @@ size_t gemm_workspace_bytes(size_t P, size_t Q, size_t R, int pipe) {
   return pl.nsplit > 1 ? (size_t)pl.nsplit * P * Q * sizeof(uint32_t) : 0;
 }
 
-size_t gemm_row_pitch(size_t R, int pipe) {
-  const size_t rb = pipe == PIPE_BF16 ? 2 * R : R;
-  // rows whose length is a multiple of 1 KiB would put a whole tile column on a few memory
-  // channels; one extra 128-byte line per row spreads them
-  return rb % 1024 == 0 ? rb + 128 : rb;
-}
-
 bool gemm_operands_addressable(size_t P, size_t Q, size_t R, int pipe) {
-  const size_t rb = gemm_row_pitch(R, pipe);
+  const size_t rb = pipe == PIPE_BF16 ? 2 * R : R;
   return (P + 256) * rb < (1ull << 31) && (Q + 256) * rb < (1ull << 31);
 }
 

@@ -85,8 +85,6 @@ enum Pipe {
 size_t gemm_workspace_bytes(size_t P, size_t Q, size_t R, int pipe);
 // operand matrices must stay below 2 GiB (32-bit buffer offsets with an out-of-range sentinel)
 bool gemm_operands_addressable(size_t P, size_t Q, size_t R, int pipe);
-// Row pitch (bytes) the linear entry points give the quantized operands of a product.
-size_t gemm_row_pitch(size_t R, int pipe);
 // pitch: bytes between consecutive operand rows (both operands), >= the row length.
 hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint8_t* Z, int kindZ,
                              size_t P, size_t Q, size_t R, size_t pitch, int pipe, const GemmScale& s,

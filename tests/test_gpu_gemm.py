@@ -67,6 +67,17 @@ def test_gemm_large_tiles_sampled():
             assert np.all(np.abs(got - ref) <= 7 * 2.0**-13 * ab)
 
 
+def test_gemm_bf16_exact_products_binary32_sums():
+    # bfloat16 operands holding 8-bit float grid values: the exact path of the linear entry points
+    P, Q, R = 200, 136, 272
+    X, Z = _rand_codes((P, R), L.E4M3, 7), _rand_codes((Q, R), L.E5M2, 8)
+    Xv, Zv = oracle.decode_array(L.E4M3, X), oracle.decode_array(L.E5M2, Z)
+    got = L.sr_gemm_bf16(torch.from_numpy(Xv).to(DEV).to(torch.bfloat16), torch.from_numpy(Zv).to(DEV).to(torch.bfloat16),
+                         alpha=0.25).cpu().numpy()
+    ref, ab = oracle.gemm_fwd(X, L.E4M3, 0.5, Z, L.E5M2, 0.5, want_abs=True)
+    check_product(got, ref, ab)
+
+
 def test_gemm_accumulate_beta_one():
     P, Q, R = 96, 80, 256
     X, Z = _rand_codes((P, R), L.INT8, 5), _rand_codes((Q, R), L.INT8, 6)
