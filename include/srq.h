@@ -34,7 +34,8 @@
  *     eps_i = (r16 + 1/2) / 65536 for stochastic rounding, 1/2 for round-to-nearest (Def. 2),
  *     r16 = 16-bit slice (i mod 8) of Philox4x32-10(counter = (counter_offset + i / 8) as
  *           (lo, hi, 0, 0), key = (seed lo, seed hi)), low half of output word 0 first.
- *     All of these steps are single IEEE binary32 operations (no fused multiply-add).
+ *     inv and t are single IEEE binary32 operations (no fused multiply-add); from t on, Eq. 1
+ *     is evaluated exactly (t / D, floor, fractional part, comparison with eps).
  *     NaN input gives code 0 (integers) or 0x7F (floats); +-Inf saturates to +-Qmax.
  */
 #ifndef SRQ_H
@@ -72,7 +73,7 @@ typedef enum { SRQ_SR = 0, SRQ_RTN = 1 } srq_round; /* Def. 3 / Def. 2 */
 typedef struct {
   int32_t kind;            /* srq_kind                                                       */
   int32_t round;           /* srq_round                                                      */
-  float scale;             /* Delta: positive, finite, with finite 1/scale                   */
+  float scale;             /* Delta: finite, at least 2^-100 (1/scale * 2^16 stays finite)   */
   uint32_t flags;          /* 0, or SRQ_FLAG_F8_PIPELINE (see below)                         */
   const float* scale_dev;  /* if not NULL: device pointer to the scale, read by the kernels  */
                            /* instead of `scale` (no host check is then possible)            */

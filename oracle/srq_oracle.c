@@ -33,11 +33,14 @@
  *     counter_offset + floor(i / 8), counter words (lo, hi, 0, 0), key
  *     (seed lo, seed hi); element i takes 16-bit slice i mod 8 of the four
  *     output words, low half of word 0 first.
- *   - all decisions that yield an integer code (the multiply by 1/scale, the
- *     floor, the fractional part, the comparison with eps) are taken in IEEE
- *     binary32, one rounding per operation, no fused multiply-add, because
- *     that is the precision the GPU kernels work in.  Matrix products are
- *     accumulated exactly (int64) or in binary64.
+ *   - the grid coordinate t = fl32(x * fl32(1/scale)) is IEEE binary32 (one
+ *     rounding per operation, no fused multiply-add): that is the precision
+ *     the inputs and the GPU kernels work in.  From t on, Eq. 1 is evaluated
+ *     exactly: t / D, its floor, its fractional part and the comparison with
+ *     eps are taken in binary64, where each of them is exact (t has 24
+ *     significant bits and |t / D| < 2^8; the one case that rounds, a
+ *     fractional part within 2^-53 of 1, lies above every threshold either
+ *     way).  Matrix products are accumulated exactly (int64) or in binary64.
  *
  * Pins (see tests/test_oracle_*.py): Random123 known-answer vectors for
  * Philox; the worked 0.7 example of Sec. 2.2.1; the closed-form count of
@@ -212,11 +215,12 @@ uint8_t srq_oracle_quantize_one(float x, float inv, int kind, float eps) {
     }
     D = ldexpf(1.0f, e - m);
   }
-  /* Eq. 1 with Delta = D */
-  float y = t / D; /* exact: D is a power of two */
-  float fl = floorf(y);
-  float frac = y - fl;
-  float q = (frac < eps) ? fl : fl + 1.0f; /* floor(y + 1) = floor(y) + 1 */
+  /* Eq. 1 with Delta = D, evaluated exactly (binary64) on the binary32 coordinate t */
+  double y = (double)t / (double)D; /* exact: D is a power of two */
+  double fl = floor(y);
+  double frac = y - fl;
+  double qd = (frac < (double)eps) ? fl : fl + 1.0; /* floor(y + 1) = floor(y) + 1 */
+  float q = (float)qd;                              /* a small integer */
   return encode_on_grid(kind, q * D);
 }
 

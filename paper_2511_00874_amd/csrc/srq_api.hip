@@ -24,7 +24,7 @@ int check_quant(const srq_quant* q) {
   if (q->flags & ~(uint32_t)SRQ_FLAG_F8_PIPELINE) return SRQ_ERR_FORMAT;
   if (!q->scale_dev) {
     const float s = q->scale;
-    if (!(s > 0.0f) || !std::isfinite(s) || !std::isfinite(1.0f / s)) return SRQ_ERR_FORMAT;
+    if (!(s >= 0x1p-100f) || !std::isfinite(s)) return SRQ_ERR_FORMAT;  // the kernels use (1/s) * 2^16
   }
   return SRQ_OK;
 }

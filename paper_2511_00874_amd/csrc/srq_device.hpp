@@ -1,8 +1,15 @@
 // Device-side building blocks of the SR quantizer: the counter-based random bits and the
 // per-element threshold quantizer (Def. 1 / Eq. 1, Def. 2, Def. 3) on the four target grids.
-// gfx950 only.  Every floating-point step that decides a code is one IEEE binary32
-// operation; the translation unit is built with -ffp-contract=off and the rounding-explicit
-// intrinsics are used so that no multiply-add fusion can change a decision.
+// gfx950 only.
+//
+// Arithmetic.  The grid coordinate t = fl32(x * inv) is one binary32 multiply.  From there
+// Eq. 1 is evaluated EXACTLY, in 16.16 fixed point: with y = t / D (a power-of-two scaling),
+//     threshold eps = (r + 1/2) / 2^16,   y = f + frac,  f = floor(y)
+//     round up  <=>  frac >= eps  <=>  frac * 2^16 >= r + 1/2  <=>  r < floor(frac * 2^16 + 1/2)
+// and since floor(y * 2^16 + 1/2) = f * 2^16 + floor(frac * 2^16 + 1/2) =: U,
+//     q = floor((U + 65535 - r) / 2^16)        (the carry out of the low 16 bits is "up").
+// U is one v_cvt_rpi_i32_f32 (floor(x + 1/2), exact, saturating) of y * 2^16, which is itself
+// exact.  Round-to-nearest (eps = 1/2) is  q = floor((floor(y * 2^16) + 32768) / 2^16).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -33,19 +40,32 @@ __device__ __forceinline__ void philox_block(uint64_t block, uint32_t k0, uint32
   w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
 }
 
-// 16-bit slice j (0..7) of a block: low half of word 0 first.
-__device__ __forceinline__ uint32_t r16_of(const uint32_t (&w)[4], int j) {
-  return (w[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+// floor(x + 1/2) and floor(x) as int32: exact, saturating (NaN gives INT_MAX)
+__device__ __forceinline__ int cvt_rpi(float x) {
+  int r;
+  asm("v_cvt_rpi_i32_f32 %0, %1" : "=v"(r) : "v"(x));
+  return r;
+}
+__device__ __forceinline__ int cvt_flr(float x) {
+  int r;
+  asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(r) : "v"(x));
+  return r;
 }
 
-// Threshold in (0,1): (r16 + 1/2) / 65536, exact in binary32.
-__device__ __forceinline__ float eps_of(uint32_t r16) {
-  return __builtin_fmaf((float)r16, 0x1p-16f, 0x1p-17f);
+// What is added to U before the shift: 65535 - r16 for stochastic rounding (r16 the element's
+// 16 random bits), 32768 for round-to-nearest.
+constexpr uint32_t RTN_ADDEND = 32768u;
+
+// The four addends of two output words of a Philox block (elements 4h .. 4h+3 of a group,
+// low half of the first word first).
+__device__ __forceinline__ void sr_addends(uint32_t w0, uint32_t w1, uint32_t (&add)[4]) {
+  const uint32_t n0 = ~w0, n1 = ~w1;  // 65535 - r in each half
+  add[0] = n0 & 0xFFFFu; add[1] = n0 >> 16; add[2] = n1 & 0xFFFFu; add[3] = n1 >> 16;
 }
 
 template <int KIND> struct Grid;
-template <> struct Grid<SRQ_INT8> { static constexpr bool is_float = false; static constexpr float qmax = 127.0f; };
-template <> struct Grid<SRQ_INT4> { static constexpr bool is_float = false; static constexpr float qmax = 7.0f; };
+template <> struct Grid<SRQ_INT8> { static constexpr bool is_float = false; static constexpr int qmax = 127; };
+template <> struct Grid<SRQ_INT4> { static constexpr bool is_float = false; static constexpr int qmax = 7; };
 template <> struct Grid<SRQ_E4M3> {
   static constexpr bool is_float = true; static constexpr float qmax = 448.0f;
   static constexpr int mbits = 3, emin = -6;
@@ -55,33 +75,40 @@ template <> struct Grid<SRQ_E5M2> {
   static constexpr int mbits = 2, emin = -14;
 };
 
+// Per-tensor constants of the multiply that produces the grid coordinate.
+struct InvScale {
+  float inv;    // fl32(1 / scale)
+  float inv16;  // inv * 2^16 (exact): fl32(x * inv16) = fl32(x * inv) * 2^16
+};
+
 // One element through Eq. 1 on grid KIND.  Returns the code in the low 8 bits (integers:
 // two's complement byte; INT4 values are in [-7,7], sign-extended to the byte).  With
 // AS_BF16 (8-bit float grids only) it returns instead the bfloat16 bit pattern of the grid
 // point q * D itself -- every E4M3 / E5M2 value is a normal bfloat16 number -- which is what
 // the exact (bf16 matrix pipeline) product consumes.
-template <int KIND, bool AS_BF16 = false>
-__device__ __forceinline__ uint32_t quantize_elem(float x, float inv, float eps) {
+template <int KIND, int ROUND, bool AS_BF16 = false>
+__device__ __forceinline__ uint32_t quantize_elem(float x, const InvScale& s, uint32_t addend) {
   using G = Grid<KIND>;
-  float t = __fmul_rn(x, inv);                          // grid coordinate
-  t = __builtin_amdgcn_fmed3f(t, -G::qmax, G::qmax);    // saturate (NaN fixed up below)
   uint32_t code;
   if constexpr (!G::is_float) {
     static_assert(!AS_BF16, "integer grids are stored as bytes");
-    const float fl = __builtin_floorf(t);
-    const float frac = __fsub_rn(t, fl);
-    const int q = (int)fl + (frac >= eps ? 1 : 0);      // Eq. 1: down iff frac < eps
+    constexpr int QI = G::qmax << 16;
+    const float y16 = __fmul_rn(x, s.inv16);                            // t * 2^16, D = 1
+    int u = ROUND == SRQ_SR ? cvt_rpi(y16) : cvt_flr(y16);              // saturating
+    u = min(max(u, -QI), QI);                                           // clamp t to +-Qmax
+    const int q = (u + (int)addend) >> 16;
     code = (uint32_t)q & 0xFFu;
     if (x != x) code = 0u;
   } else {
+    float t = __fmul_rn(x, s.inv);                                      // grid coordinate
+    t = __builtin_amdgcn_fmed3f(t, -G::qmax, G::qmax);                  // saturate (NaN fixed up below)
     // spacing of the grid at t: D = 2^(e - m), e = max(floor(log2|t|), emin)
     const uint32_t a = __float_as_uint(t) & 0x7FFFFFFFu;
-    const int eb = max((int)(a >> 23), G::emin + 127);  // biased e (0 and subnormals clamp)
-    const float inv_d = __uint_as_float((uint32_t)(254 + G::mbits - eb) << 23);  // 2^(m - e)
-    const float y = __fmul_rn(t, inv_d);                // exact: power-of-two scaling
-    const float fl = __builtin_floorf(y);
-    const float frac = __fsub_rn(y, fl);
-    const int q = (int)fl + (frac >= eps ? 1 : 0);      // |q| in [0, 2^(m+1)]
+    const int eb = max((int)(a >> 23), G::emin + 127);                  // biased e (0 and subnormals clamp)
+    const float up16 = __uint_as_float((uint32_t)(270 + G::mbits - eb) << 23);  // 2^(16 + m - e)
+    const float y16 = __fmul_rn(t, up16);                               // (t / D) * 2^16, exact
+    const int u = ROUND == SRQ_SR ? cvt_rpi(y16) : cvt_flr(y16);
+    const int q = (u + (int)addend) >> 16;                              // |q| in [0, 2^(m+1)]
     if constexpr (AS_BF16) {
       const float d = __uint_as_float((uint32_t)(eb - G::mbits) << 23);  // D = 2^(e - m)
       code = __float_as_uint(__fmul_rn((float)q, d)) >> 16;             // exact, <= 4 significant bits
@@ -100,9 +127,12 @@ __device__ __forceinline__ uint32_t quantize_elem(float x, float inv, float eps)
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
 // 1 / scale, correctly rounded, from a host value or a device-resident one.
-__device__ __forceinline__ float inv_scale(float scale, const float* scale_dev) {
-  const float s = scale_dev ? *scale_dev : scale;
-  return __fdiv_rn(1.0f, s);
+__device__ __forceinline__ InvScale inv_scale(float scale, const float* scale_dev) {
+  const float sc = scale_dev ? *scale_dev : scale;
+  InvScale s;
+  s.inv = __fdiv_rn(1.0f, sc);
+  s.inv16 = __fmul_rn(s.inv, 65536.0f);
+  return s;
 }
 
 // ---- groups of 8 consecutive elements (one Philox block) -----------------------------------
@@ -144,16 +174,78 @@ __device__ __forceinline__ void load_group(float (&v)[8], const void* x, size_t 
 
 // Quantize one group; c[j] = code byte of element j.
 template <int KIND, int ROUND, bool AS_BF16>
-__device__ __forceinline__ void quantize_group(uint32_t (&c)[8], const float (&v)[8], float inv,
+__device__ __forceinline__ void quantize_group(uint32_t (&c)[8], const float (&v)[8], const InvScale& s,
                                                uint64_t block, uint32_t k0, uint32_t k1) {
+  uint32_t add[8];
   if constexpr (ROUND == SRQ_SR) {
     uint32_t w[4];
     philox_block(block, k0, k1, w);
+    uint32_t lo[4], hi[4];
+    sr_addends(w[0], w[1], lo);
+    sr_addends(w[2], w[3], hi);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, AS_BF16>(v[j], inv, eps_of(r16_of(w, j)));
+    for (int j = 0; j < 4; ++j) { add[j] = lo[j]; add[4 + j] = hi[j]; }
   } else {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, AS_BF16>(v[j], inv, 0.5f);  // Def. 2
+    for (int j = 0; j < 8; ++j) add[j] = RTN_ADDEND;  // Def. 2
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, ROUND, AS_BF16>(v[j], s, add[j]);
+}
+
+// ---- one wave, 512 consecutive binary32 elements, fully coalesced ---------------------------
+// Lane L loads elements 4L..4L+3 of the chunk and 256+4L..256+4L+3: two 16-byte loads, each a
+// contiguous kilobyte across the wave.  A lane therefore holds one half of Philox group L/2 and
+// one half of group 32 + L/2.  The even lane of a pair draws the block of the first group, the
+// odd lane the block of the second, and they trade the two words the other needs through a
+// quad permute: one Philox block per 8 elements, as in the layout-free definition.
+constexpr int CHUNK = 512;
+
+// store modes: 0 one byte per element, 1 nibbles, 2 bfloat16 (values as in StoreMode)
+template <int KIND, int ROUND, int STORE>
+__device__ __forceinline__ void quantize_chunk_f32(uint8_t* __restrict__ out, const float* __restrict__ x,
+                                                   size_t chunk, uint32_t lane, const InvScale& s, uint32_t k0,
+                                                   uint32_t k1, uint64_t counter_offset) {
+  constexpr bool AS_BF16 = STORE == 2;
+  const size_t e0 = chunk * CHUNK + 4 * lane;  // first element of this lane's first quad
+  const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x + e0));
+  const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x + e0 + 256));
+  uint32_t addA[4], addB[4];
+  if constexpr (ROUND == SRQ_SR) {
+    const bool odd = lane & 1u;
+    uint32_t w[4];
+    philox_block(counter_offset + chunk * (CHUNK / 8) + (odd ? 32u : 0u) + (lane >> 1), k0, k1, w);
+    // Even lane: its first quad is the first half of its own block (words 0,1), its second quad
+    // the first half of the odd neighbour's block.  Odd lane: first quad = second half (words
+    // 2,3) of the even neighbour's block, second quad = second half of its own.
+    const uint32_t nb0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[0], 0xB1, 0xF, 0xF, true);  // lane ^ 1
+    const uint32_t nb1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[1], 0xB1, 0xF, 0xF, true);
+    const uint32_t nb2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[2], 0xB1, 0xF, 0xF, true);
+    const uint32_t nb3 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[3], 0xB1, 0xF, 0xF, true);
+    sr_addends(odd ? nb2 : w[0], odd ? nb3 : w[1], addA);
+    sr_addends(odd ? w[2] : nb0, odd ? w[3] : nb1, addB);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) addA[j] = addB[j] = RTN_ADDEND;  // Def. 2
+  }
+  uint32_t ca[4], cb[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    ca[j] = quantize_elem<KIND, ROUND, AS_BF16>(a[j], s, addA[j]);
+    cb[j] = quantize_elem<KIND, ROUND, AS_BF16>(b[j], s, addB[j]);
+  }
+  if constexpr (STORE == 1) {
+    uint16_t* o = reinterpret_cast<uint16_t*>(out + e0 / 2);
+    o[0] = (uint16_t)((ca[0] & 0xFu) | ((ca[1] & 0xFu) << 4) | ((ca[2] & 0xFu) << 8) | ((ca[3] & 0xFu) << 12));
+    o[64] = (uint16_t)((cb[0] & 0xFu) | ((cb[1] & 0xFu) << 4) | ((cb[2] & 0xFu) << 8) | ((cb[3] & 0xFu) << 12));
+  } else if constexpr (STORE == 2) {
+    u32x2* o = reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + e0);
+    __builtin_nontemporal_store(u32x2{ca[0] | (ca[1] << 16), ca[2] | (ca[3] << 16)}, o);
+    __builtin_nontemporal_store(u32x2{cb[0] | (cb[1] << 16), cb[2] | (cb[3] << 16)}, o + 64);
+  } else {
+    uint32_t* o = reinterpret_cast<uint32_t*>(out + e0);
+    __builtin_nontemporal_store(ca[0] | (ca[1] << 8) | (ca[2] << 16) | (ca[3] << 24), o);
+    __builtin_nontemporal_store(cb[0] | (cb[1] << 8) | (cb[2] << 16) | (cb[3] << 24), o + 64);
   }
 }
 

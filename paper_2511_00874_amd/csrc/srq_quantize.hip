@@ -27,7 +27,7 @@ __global__ __launch_bounds__(QBLOCK) void quantize_flat_kernel(uint8_t* __restri
                                                                const void* __restrict__ x, size_t n,
                                                                float scale, const float* scale_dev,
                                                                uint64_t seed, uint64_t counter_offset) {
-  const float inv = inv_scale(scale, scale_dev);
+  const InvScale inv = inv_scale(scale, scale_dev);
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
   const size_t ngroups = (n + 7) / 8;
   const size_t stride = (size_t)gridDim.x * QBLOCK;
@@ -67,6 +67,21 @@ __global__ __launch_bounds__(QBLOCK) void quantize_flat_kernel(uint8_t* __restri
   }
 }
 
+// binary32 source, whole 512-element chunks: one chunk per wave, fully coalesced (see
+// quantize_chunk_f32); the ragged remainder goes to quantize_flat_kernel
+template <int KIND, int ROUND, int STORE>
+__global__ __launch_bounds__(QBLOCK) void quantize_flat_f32_kernel(uint8_t* __restrict__ out,
+                                                                   const float* __restrict__ x, size_t nchunks,
+                                                                   float scale, const float* scale_dev,
+                                                                   uint64_t seed, uint64_t counter_offset) {
+  const InvScale inv = inv_scale(scale, scale_dev);
+  const uint32_t lane = threadIdx.x & 63u;
+  const size_t waves = (size_t)gridDim.x * (QBLOCK / 64);
+  for (size_t c = (size_t)blockIdx.x * (QBLOCK / 64) + (threadIdx.x >> 6); c < nchunks; c += waves)
+    quantize_chunk_f32<KIND, ROUND, STORE>(out, x, c, lane, inv, (uint32_t)seed, (uint32_t)(seed >> 32),
+                                           counter_offset);
+}
+
 // ---- transposed output --------------------------------------------------------------------
 // A block quantizes a TR x TC tile (thresholds keyed by the row-major SOURCE index, so the
 // codes equal those of the same-layout kernel), turns it through LDS, and writes it as
@@ -82,7 +97,7 @@ __global__ __launch_bounds__(QBLOCK) void quantize_transpose_kernel(
   constexpr int ES = sizeof(elem_t);
   constexpr int PITCH = TR + 4 / ES;            // elements; keeps rows 4-byte aligned
   __shared__ __attribute__((aligned(16))) elem_t tile[TC * PITCH];
-  const float inv = inv_scale(scale, scale_dev);
+  const InvScale inv = inv_scale(scale, scale_dev);
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
   const uint32_t r0 = blockIdx.y * TR, c0 = blockIdx.x * TC;
   const size_t n = (size_t)rows * cols;
@@ -273,10 +288,26 @@ hipError_t launch_one(void* codes, const void* x, size_t rows, size_t cols, int 
         a.counter_offset);
   } else {
     const size_t n = rows * cols;
-    // a few groups per thread: enough loads in flight per wave, small tail
-    const int grid = grid_for((n + 7) / 8, QBLOCK * 4, 1 << 20);
-    quantize_flat_kernel<KIND, SRC, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
-        static_cast<uint8_t*>(codes), x, n, a.scale, a.scale_dev, a.seed, a.counter_offset);
+    size_t done = 0;  // elements handled by the coalesced chunk kernel
+    if constexpr (SRC == SRQ_F32) {
+      const size_t nchunks = n / CHUNK;
+      if (nchunks > 0) {
+        const int grid = grid_for(nchunks, QBLOCK / 64, 1 << 22);
+        quantize_flat_f32_kernel<KIND, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
+            static_cast<uint8_t*>(codes), static_cast<const float*>(x), nchunks, a.scale, a.scale_dev, a.seed,
+            a.counter_offset);
+        done = nchunks * CHUNK;
+      }
+    }
+    if (done < n) {
+      // remainder (or a bfloat16 source, whose groups are one 16-byte load each already)
+      const size_t es = SRC == SRQ_F32 ? 4 : 2;
+      const size_t out_bytes = STORE == STORE_NIBBLE ? done / 2 : STORE == STORE_BF16 ? done * 2 : done;
+      const int grid = grid_for((n - done + 7) / 8, QBLOCK * 4, 1 << 20);
+      quantize_flat_kernel<KIND, SRC, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
+          static_cast<uint8_t*>(codes) + out_bytes, static_cast<const uint8_t*>(x) + done * es, n - done, a.scale,
+          a.scale_dev, a.seed, a.counter_offset + done / 8);
+    }
   }
   return hipGetLastError();
 }

@@ -14,10 +14,10 @@ namespace {
 
 constexpr int QBLOCK = 256;
 constexpr int TR = 128, TC = 64;        // transposing tile: TR source rows x TC source columns
-constexpr int FLAT_GROUPS_PER_BLOCK = QBLOCK * 4;
+constexpr int FLAT_GROUPS_PER_BLOCK = QBLOCK;  // four 512-element chunks: one per wave
 
 template <int KIND, bool AS_BF16>
-__device__ __forceinline__ void job_quantize_group(uint32_t (&c)[8], const float (&v)[8], float inv,
+__device__ __forceinline__ void job_quantize_group(uint32_t (&c)[8], const float (&v)[8], const InvScale& inv,
                                                    const QuantJob& j, uint64_t g, uint32_t k0, uint32_t k1) {
   if (j.round == SRQ_SR) quantize_group<KIND, SRQ_SR, AS_BF16>(c, v, inv, j.counter_offset + g, k0, k1);
   else quantize_group<KIND, SRQ_RTN, AS_BF16>(c, v, inv, 0, 0, 0);
@@ -40,13 +40,27 @@ __device__ __forceinline__ void store_group(uint8_t* out, size_t base, const uin
   }
 }
 
-// same layout as the source; rows * cols is a multiple of 8 for the linear entry points
+// same layout as the source; rows * cols is a multiple of 8 for the linear entry points.
+// binary32 sources go chunk-wise (one fully coalesced 512-element chunk per wave at a time),
+// what is left over, and bfloat16 sources, group-wise.
 template <int KIND, bool AS_BF16>
 __device__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
-  const float inv = inv_scale(j.scale, j.scale_dev);
+  const InvScale inv = inv_scale(j.scale, j.scale_dev);
   const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
   const size_t n = (size_t)j.rows * j.cols, ngroups = n / 8;
-  for (size_t g = (size_t)local * QBLOCK + threadIdx.x; g < ngroups; g += (size_t)nblocks * QBLOCK) {
+  size_t first_group = 0;
+  if (j.dtype == SRQ_F32) {
+    const size_t nchunks = n / CHUNK, waves = (size_t)nblocks * (QBLOCK / 64);
+    const float* x = static_cast<const float*>(j.x);
+    for (size_t c = (size_t)local * (QBLOCK / 64) + (threadIdx.x >> 6); c < nchunks; c += waves) {
+      if (j.round == SRQ_SR)
+        quantize_chunk_f32<KIND, SRQ_SR, AS_BF16 ? 2 : 0>(j.out, x, c, threadIdx.x & 63u, inv, k0, k1, j.counter_offset);
+      else
+        quantize_chunk_f32<KIND, SRQ_RTN, AS_BF16 ? 2 : 0>(j.out, x, c, threadIdx.x & 63u, inv, k0, k1, j.counter_offset);
+    }
+    first_group = nchunks * (CHUNK / 8);
+  }
+  for (size_t g = first_group + (size_t)local * QBLOCK + threadIdx.x; g < ngroups; g += (size_t)nblocks * QBLOCK) {
     float v[8];
     uint32_t c[8];
     job_load_group(v, j, g, n);
@@ -62,7 +76,7 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
   constexpr int ES = sizeof(elem_t);
   constexpr int PITCH = TR + 4 / ES;
   elem_t* tile = reinterpret_cast<elem_t*>(smem);
-  const float inv = inv_scale(j.scale, j.scale_dev);
+  const InvScale inv = inv_scale(j.scale, j.scale_dev);
   const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
   const uint32_t tiles_x = (j.cols + TC - 1) / TC;
   const uint32_t r0 = (local / tiles_x) * TR, c0 = (local % tiles_x) * TC;

@@ -65,6 +65,21 @@ def test_transposed_codes_equal_the_same_codes_transposed(kind, shape):
     assert np.array_equal(got_rm, oracle_codes(xd, kind, scale, 11, 77))
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_thresholds_scanned_on_hard_constants(kind):
+    # each constant meets ~2^17 different thresholds: values whose fractional part is not a
+    # binary32 number (negative coordinates), neighbours of 1/2 ulp traps, tiny magnitudes
+    consts = np.float32([-0.3, 0.3, -0.7, -1e-3, (0.5 - 2.0**-25) / 65536.0, -(0.5 - 2.0**-25) / 65536.0,
+                         -126.99999, 126.99999, -5.0000005, 2.0**-7 * 1.2345, -(2.0**-7) * 1.2345,
+                         2.0**-17, -(2.0**-17), 1.0 - 2.0**-24, -(1.0 - 2.0**-24), 0.49999997])
+    x = np.repeat(consts, 1 << 17)
+    xd = to_dev(x)
+    got = L.sr_quantize(xd, L.Quant(kind, 1.0, seed=77, counter_offset=5)).cpu().numpy()
+    assert np.array_equal(got, oracle_codes(xd, kind, 1.0, 77, 5))
+    got = L.sr_quantize(xd, L.Quant(kind, 1.0, round_mode=L.RTN)).cpu().numpy()
+    assert np.array_equal(got, oracle_codes(xd, kind, 1.0, 0, 0, oracle.RTN))
+
+
 def test_bf16_transposed():
     x = synth.gaussian((256, 136), 0.02, 5)
     xd = to_dev(x, bf16=True)
