@@ -28,8 +28,8 @@ __device__ __forceinline__ void philox_block(uint64_t block, uint32_t k0, uint32
   for (int round = 0; round < 10; ++round) {
     const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
     const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
-    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);  // three-way xor
+    const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
     c1 = (uint32_t)p1;
     c3 = (uint32_t)p0;
     c0 = n0;
@@ -86,7 +86,9 @@ struct InvScale {
 // AS_BF16 (8-bit float grids only) it returns instead the bfloat16 bit pattern of the grid
 // point q * D itself -- every E4M3 / E5M2 value is a normal bfloat16 number -- which is what
 // the exact (bf16 matrix pipeline) product consumes.
-template <int KIND, int ROUND, bool AS_BF16 = false>
+// FIX_NAN = false leaves the NaN rule to the caller (quantize_quad applies it per quad).
+// Integer codes come back sign-extended to 32 bits: take the low byte (or nibble).
+template <int KIND, int ROUND, bool AS_BF16 = false, bool FIX_NAN = true>
 __device__ __forceinline__ uint32_t quantize_elem(float x, const InvScale& s, uint32_t addend) {
   using G = Grid<KIND>;
   uint32_t code;
@@ -97,8 +99,8 @@ __device__ __forceinline__ uint32_t quantize_elem(float x, const InvScale& s, ui
     int u = ROUND == SRQ_SR ? cvt_rpi(y16) : cvt_flr(y16);              // saturating
     u = min(max(u, -QI), QI);                                           // clamp t to +-Qmax
     const int q = (u + (int)addend) >> 16;
-    code = (uint32_t)q & 0xFFu;
-    if (x != x) code = 0u;
+    code = (uint32_t)q;
+    if (FIX_NAN && x != x) code = 0u;
   } else {
     float t = __fmul_rn(x, s.inv);                                      // grid coordinate
     t = __builtin_amdgcn_fmed3f(t, -G::qmax, G::qmax);                  // saturate (NaN fixed up below)
@@ -112,16 +114,45 @@ __device__ __forceinline__ uint32_t quantize_elem(float x, const InvScale& s, ui
     if constexpr (AS_BF16) {
       const float d = __uint_as_float((uint32_t)(eb - G::mbits) << 23);  // D = 2^(e - m)
       code = __float_as_uint(__fmul_rn((float)q, d)) >> 16;             // exact, <= 4 significant bits
-      if (x != x) code = 0x7FC0u;
+      if (FIX_NAN && x != x) code = 0x7FC0u;
     } else {
       // sign | ((e - emin) << m) + |q| : covers subnormals (field 0), normals (the hidden one
       // of |q| bumps the field) and the carry into the next binade
       const uint32_t mag = ((uint32_t)(eb - (G::emin + 127)) << G::mbits) + (uint32_t)abs(q);
       code = mag | (q < 0 ? 0x80u : 0u);
-      if (x != x) code = 0x7Fu;
+      if (FIX_NAN && x != x) code = 0x7Fu;
     }
   }
   return code;
+}
+
+// Four elements.  The NaN rule is tested for the quad as a whole (two unordered compares)
+// and applied element-wise only on the rare lanes where it fires.
+template <int KIND, int ROUND, bool AS_BF16>
+__device__ __forceinline__ void quantize_quad(uint32_t (&c)[4], float x0, float x1, float x2, float x3,
+                                              const InvScale& s, const uint32_t (&add)[4]) {
+  c[0] = quantize_elem<KIND, ROUND, AS_BF16, false>(x0, s, add[0]);
+  c[1] = quantize_elem<KIND, ROUND, AS_BF16, false>(x1, s, add[1]);
+  c[2] = quantize_elem<KIND, ROUND, AS_BF16, false>(x2, s, add[2]);
+  c[3] = quantize_elem<KIND, ROUND, AS_BF16, false>(x3, s, add[3]);
+  if (__builtin_isunordered(x0, x1) || __builtin_isunordered(x2, x3)) {
+    constexpr uint32_t NAN_CODE = !Grid<KIND>::is_float ? 0u : AS_BF16 ? 0x7FC0u : 0x7Fu;
+    if (x0 != x0) c[0] = NAN_CODE;
+    if (x1 != x1) c[1] = NAN_CODE;
+    if (x2 != x2) c[2] = NAN_CODE;
+    if (x3 != x3) c[3] = NAN_CODE;
+  }
+}
+
+// low bytes of four codes -> one word (c0 in bits 7:0); upper bits of the inputs are ignored
+__device__ __forceinline__ uint32_t pack4_bytes(const uint32_t (&c)[4]) {
+  const uint32_t lo = __builtin_amdgcn_perm(c[1], c[0], 0x0c0c0400u);
+  const uint32_t hi = __builtin_amdgcn_perm(c[3], c[2], 0x0c0c0400u);
+  return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+// low nibbles of four codes -> 16 bits (c0 in bits 3:0)
+__device__ __forceinline__ uint32_t pack4_nibbles(const uint32_t (&c)[4]) {
+  return (c[0] & 0xFu) | ((c[1] & 0xFu) << 4) | ((c[2] & 0xFu) << 8) | ((c[3] & 0xFu) << 12);
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
@@ -172,7 +203,7 @@ __device__ __forceinline__ void load_group(float (&v)[8], const void* x, size_t 
   }
 }
 
-// Quantize one group; c[j] = code byte of element j.
+// Quantize one group; c[j] = code of element j (integer codes sign-extended: use the low byte).
 template <int KIND, int ROUND, bool AS_BF16>
 __device__ __forceinline__ void quantize_group(uint32_t (&c)[8], const float (&v)[8], const InvScale& s,
                                                uint64_t block, uint32_t k0, uint32_t k1) {
@@ -189,8 +220,12 @@ __device__ __forceinline__ void quantize_group(uint32_t (&c)[8], const float (&v
 #pragma unroll
     for (int j = 0; j < 8; ++j) add[j] = RTN_ADDEND;  // Def. 2
   }
+  uint32_t lo4[4], hi4[4];
+  const uint32_t addlo[4] = {add[0], add[1], add[2], add[3]}, addhi[4] = {add[4], add[5], add[6], add[7]};
+  quantize_quad<KIND, ROUND, AS_BF16>(lo4, v[0], v[1], v[2], v[3], s, addlo);
+  quantize_quad<KIND, ROUND, AS_BF16>(hi4, v[4], v[5], v[6], v[7], s, addhi);
 #pragma unroll
-  for (int j = 0; j < 8; ++j) c[j] = quantize_elem<KIND, ROUND, AS_BF16>(v[j], s, add[j]);
+  for (int j = 0; j < 4; ++j) { c[j] = lo4[j]; c[4 + j] = hi4[j]; }
 }
 
 // ---- one wave, 512 consecutive binary32 elements, fully coalesced ---------------------------
@@ -229,23 +264,20 @@ __device__ __forceinline__ void quantize_chunk_f32(uint8_t* __restrict__ out, co
     for (int j = 0; j < 4; ++j) addA[j] = addB[j] = RTN_ADDEND;  // Def. 2
   }
   uint32_t ca[4], cb[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    ca[j] = quantize_elem<KIND, ROUND, AS_BF16>(a[j], s, addA[j]);
-    cb[j] = quantize_elem<KIND, ROUND, AS_BF16>(b[j], s, addB[j]);
-  }
+  quantize_quad<KIND, ROUND, AS_BF16>(ca, a.x, a.y, a.z, a.w, s, addA);
+  quantize_quad<KIND, ROUND, AS_BF16>(cb, b.x, b.y, b.z, b.w, s, addB);
   if constexpr (STORE == 1) {
     uint16_t* o = reinterpret_cast<uint16_t*>(out + e0 / 2);
-    o[0] = (uint16_t)((ca[0] & 0xFu) | ((ca[1] & 0xFu) << 4) | ((ca[2] & 0xFu) << 8) | ((ca[3] & 0xFu) << 12));
-    o[64] = (uint16_t)((cb[0] & 0xFu) | ((cb[1] & 0xFu) << 4) | ((cb[2] & 0xFu) << 8) | ((cb[3] & 0xFu) << 12));
+    o[0] = (uint16_t)pack4_nibbles(ca);
+    o[64] = (uint16_t)pack4_nibbles(cb);
   } else if constexpr (STORE == 2) {
     u32x2* o = reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + e0);
     __builtin_nontemporal_store(u32x2{ca[0] | (ca[1] << 16), ca[2] | (ca[3] << 16)}, o);
     __builtin_nontemporal_store(u32x2{cb[0] | (cb[1] << 16), cb[2] | (cb[3] << 16)}, o + 64);
   } else {
     uint32_t* o = reinterpret_cast<uint32_t*>(out + e0);
-    __builtin_nontemporal_store(ca[0] | (ca[1] << 8) | (ca[2] << 16) | (ca[3] << 24), o);
-    __builtin_nontemporal_store(cb[0] | (cb[1] << 8) | (cb[2] << 16) | (cb[3] << 24), o + 64);
+    __builtin_nontemporal_store(pack4_bytes(ca), o);
+    __builtin_nontemporal_store(pack4_bytes(cb), o + 64);
   }
 }
 

@@ -12,7 +12,8 @@ namespace {
 constexpr int QBLOCK = 256;
 
 __device__ __forceinline__ uint32_t pack_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
-  return a | (b << 8) | (c << 16) | (d << 24);
+  const uint32_t q[4] = {a, b, c, d};
+  return pack4_bytes(q);
 }
 __device__ __forceinline__ uint32_t pack_nibbles(const uint32_t (&c)[8]) {
   uint32_t r = 0;

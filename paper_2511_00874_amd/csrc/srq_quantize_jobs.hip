@@ -35,7 +35,8 @@ __device__ __forceinline__ void store_group(uint8_t* out, size_t base, const uin
     u32x4 w = {c[0] | (c[1] << 16), c[2] | (c[3] << 16), c[4] | (c[5] << 16), c[6] | (c[7] << 16)};
     *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + base) = w;
   } else {
-    u32x2 w = {c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24), c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24)};
+    const uint32_t lo[4] = {c[0], c[1], c[2], c[3]}, hi[4] = {c[4], c[5], c[6], c[7]};
+    u32x2 w = {pack4_bytes(lo), pack4_bytes(hi)};
     *reinterpret_cast<u32x2*>(out + base) = w;
   }
 }
