@@ -27,8 +27,8 @@ FWD_KIND, BWD_KIND = "int8", "e5m2"
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-quantizer-sweep", action="store_true")
     return ap.parse_args()
@@ -84,10 +84,20 @@ def time_steps(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
-def event_ms(torch, fn, reps, warmup=3):
-    """Average duration of fn's launches on the current stream, by HIP events."""
-    for _ in range(warmup):
-        fn()
+def event_ms(torch, fn, reps, warmup=3, warm_ms=30.0):
+    """Average duration of fn's launches on the current stream, by HIP events.  Warm-up runs
+    until `warm_ms` of GPU time has passed: after an idle gap the clocks take a while to ramp."""
+    w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    w0.record()
+    done = 0
+    while True:
+        for _ in range(warmup):
+            fn()
+        done += warmup
+        w1.record()
+        w1.synchronize()
+        if w0.elapsed_time(w1) >= warm_ms or done > 10000:
+            break
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     for _ in range(reps):

@@ -177,20 +177,44 @@ __device__ __forceinline__ uint32_t abs_bits_finite(float f) {
   return a < 0x7F800000u ? a : 0u;
 }
 
+// max of the finite |x_i| bit patterns over the elements this thread takes of x[0, n): thread
+// `tid` of `nthreads`, 16-byte loads that are contiguous across the wave (the order of the
+// elements does not matter for a maximum)
+template <int SRC>
+__device__ __forceinline__ uint32_t absmax_slice(const void* __restrict__ x, size_t n, size_t tid, size_t nthreads) {
+  uint32_t m = 0u;
+  if constexpr (SRC == SRQ_F32) {
+    const f32x4* p = static_cast<const f32x4*>(x);
+    const size_t n4 = n / 4;
+    auto fold = [&](const f32x4& a) {
+      m = max(max(m, max(abs_bits_finite(a.x), abs_bits_finite(a.y))), max(abs_bits_finite(a.z), abs_bits_finite(a.w)));
+    };
+    size_t i = tid;
+    for (; i + 3 * nthreads < n4; i += 4 * nthreads) {  // four loads in flight per lane
+      const f32x4 a = __builtin_nontemporal_load(p + i), b = __builtin_nontemporal_load(p + i + nthreads);
+      const f32x4 c = __builtin_nontemporal_load(p + i + 2 * nthreads), d = __builtin_nontemporal_load(p + i + 3 * nthreads);
+      fold(a); fold(b); fold(c); fold(d);
+    }
+    for (; i < n4; i += nthreads) fold(__builtin_nontemporal_load(p + i));
+    if (tid < n - n4 * 4) m = max(m, abs_bits_finite(static_cast<const float*>(x)[n4 * 4 + tid]));
+  } else {
+    const size_t ngroups = (n + 7) / 8;
+    for (size_t g = tid; g < ngroups; g += nthreads) {
+      float v[8];
+      load_group<SRQ_BF16>(v, x, g, n);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) m = max(m, abs_bits_finite(v[j]));
+    }
+  }
+  return m;
+}
+
 __global__ void absmax_init_kernel(uint32_t* acc) { *acc = 0u; }
 
 template <int SRC>
 __global__ __launch_bounds__(QBLOCK) void absmax_kernel(uint32_t* __restrict__ acc,
                                                         const void* __restrict__ x, size_t n) {
-  uint32_t m = 0u;
-  const size_t ngroups = (n + 7) / 8;
-  const size_t stride = (size_t)gridDim.x * QBLOCK;
-  for (size_t g = (size_t)blockIdx.x * QBLOCK + threadIdx.x; g < ngroups; g += stride) {
-    float v[8];
-    load_group<SRC>(v, x, g, n);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) m = max(m, abs_bits_finite(v[j]));
-  }
+  uint32_t m = absmax_slice<SRC>(x, n, (size_t)blockIdx.x * QBLOCK + threadIdx.x, (size_t)gridDim.x * QBLOCK);
   m = wave_umax(m);
   __shared__ uint32_t part[QBLOCK / 64];
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
@@ -220,15 +244,9 @@ __global__ __launch_bounds__(QBLOCK) void absmax_multi_kernel(AbsmaxBatch b) {
   const uint32_t local = blockIdx.x - b.first_block[t], nblk = b.nblocks[t];
   const size_t n = b.n[t];
   const void* x = b.x[t];
-  const size_t ngroups = (n + 7) / 8;
-  uint32_t m = 0u;
-  for (size_t g = (size_t)local * QBLOCK + threadIdx.x; g < ngroups; g += (size_t)nblk * QBLOCK) {
-    float v[8];
-    if (b.dtype[t] == SRQ_F32) load_group<SRQ_F32>(v, x, g, n);
-    else load_group<SRQ_BF16>(v, x, g, n);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) m = max(m, abs_bits_finite(v[j]));
-  }
+  const size_t tid = (size_t)local * QBLOCK + threadIdx.x, nthreads = (size_t)nblk * QBLOCK;
+  uint32_t m = b.dtype[t] == SRQ_F32 ? absmax_slice<SRQ_F32>(x, n, tid, nthreads)
+                                     : absmax_slice<SRQ_BF16>(x, n, tid, nthreads);
   m = wave_umax(m);
   __shared__ uint32_t part[QBLOCK / 64];
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
@@ -348,14 +366,14 @@ hipError_t launch_quantize(void* codes, const void* x, size_t rows, size_t cols,
 }
 
 size_t absmax_batch_plan(AbsmaxBatch& b) {
-  // about eight workgroups per CU in total, shared out by size; at least one per tensor
+  // about eight 16-byte loads per lane, at most 32768 workgroups in all; at least one per tensor
   size_t total_groups = 0;
   for (int t = 0; t < b.ntensors; ++t) total_groups += (b.n[t] + 7) / 8;
   uint32_t first = 0;
   for (int t = 0; t < b.ntensors; ++t) {
     const size_t groups = (b.n[t] + 7) / 8;
     size_t nb = (groups + QBLOCK * 4 - 1) / (QBLOCK * 4);
-    const size_t share = total_groups ? (2048 * groups + total_groups - 1) / total_groups : 1;
+    const size_t share = total_groups ? (32768 * groups + total_groups - 1) / total_groups : 1;
     if (nb > share) nb = share;
     if (nb < 1) nb = 1;
     b.first_block[t] = first;
@@ -378,7 +396,7 @@ hipError_t launch_absmax_scale(float* scale_out_dev, const void* x, int dtype, s
   uint32_t* acc = reinterpret_cast<uint32_t*>(scale_out_dev);
   absmax_init_kernel<<<1, 1, 0, stream>>>(acc);
   if (n > 0) {
-    const int grid = grid_for((n + 7) / 8, QBLOCK * 8, 4096);
+    const int grid = grid_for((n + 7) / 8, QBLOCK * 4, 2048);  // one atomic per workgroup: keep them few
     if (dtype == SRQ_F32) absmax_kernel<SRQ_F32><<<grid, QBLOCK, 0, stream>>>(acc, x, n);
     else absmax_kernel<SRQ_BF16><<<grid, QBLOCK, 0, stream>>>(acc, x, n);
   }
