@@ -19,6 +19,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by what the same counters
+# read for a plain copy of known size (profiles/bench_hbm_traffic.txt): mean over the three
+# launches per step of the bf16 128 x 128 product kernel, and the int8 quantizer on 2^28 elements
+TRAFFIC_BF16_PRODUCT_128 = (2 * (228.7 + 18.0) + (123.5 + 96.0)) / 3 * 2**20
+TRAFFIC_QUANTIZE_INT8_2P28 = (1024.0 + 256.0) * 2**20
 MFMA_PEAK_TFLOPS = {"int8": 5000.0, "fp8": 5000.0, "bf16": 2500.0}
 TOKENS = 8192
 FWD_KIND, BWD_KIND = "int8", "e5m2"
@@ -31,6 +36,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-quantizer-sweep", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB -> 1 GiB device copy (known HBM traffic, to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -144,9 +152,12 @@ def product_kernel_rooflines(L, torch, layers, reps):
 
     fwd_shapes = [(ly.M, ly.N, ly.K) for ly in layers]
     bwd_shapes = [s for ly in layers for s in ((ly.M, ly.K, ly.N), (ly.N, ly.K, ly.M))]
+    # the backward products that run the 128 x 128-tile instantiation (the 8192 x 768 output of
+    # fc1's input gradient takes the 128 x 192 one): fc2's input gradient and both weight gradients
+    bwd128 = [s for s in bwd_shapes if not (s[0] == TOKENS and s[1] == 768)]
     for name, shapes, make, call, need_fn, peak, kernel in (
-            ("bf16", bwd_shapes, bf, lambda X, Z, o, ws: L.sr_gemm_bf16(X, Z, out=o, workspace=ws),
-             L.raw.sr_gemm_bf16_workspace_bytes, MFMA_PEAK_TFLOPS["bf16"], "gemm_nt_kernel<BF16Mma, 128, ...>"),
+            ("bf16", bwd128, bf, lambda X, Z, o, ws: L.sr_gemm_bf16(X, Z, out=o, workspace=ws),
+             L.raw.sr_gemm_bf16_workspace_bytes, MFMA_PEAK_TFLOPS["bf16"], "gemm_nt_kernel<BF16Mma, 128, 128, 2, 2, 2>"),
             ("int8", fwd_shapes, codes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.INT8, Z, L.INT8, out=o, workspace=ws),
              L.raw.sr_gemm_workspace_bytes, MFMA_PEAK_TFLOPS["int8"], "gemm_nt_kernel<I8Mma, 128, ...>"),
             ("fp8", bwd_shapes, codes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.E5M2, Z, L.E5M2, out=o, workspace=ws),
@@ -290,14 +301,24 @@ def main():
     }
     dom = rl["bf16"]
     line["roofline"] = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["TFLOP/s"], "peak": dom["peak"],
-                        "unit": "TFLOP/s", "frac": dom["frac"], "traffic": None,
-                        "note": "dominant kernel of the step by time: 4 of the 6 products; average over its 4 launches"}
+                        "unit": "TFLOP/s", "frac": dom["frac"], "traffic": round(TRAFFIC_BF16_PRODUCT_128),
+                        "note": "dominant kernel of the step by time (3 of its 6 products); 38.65 GFLOP per launch "
+                                "over the mean event-timed launch, which for the two weight-gradient launches "
+                                "includes the 6 us kernel that sums the two contraction slices; algorithmic bytes "
+                                "per launch 93.8e6, measured HBM traffic 2.7x that"}
     if not args.no_quantizer_sweep:
         qs = quantizer_sweep(L, synth, torch, max(5, args.steps // 5))
         line["sr_quantize"] = qs
-        line["roofline_quantizer"] = {"bound": "hbm", "kernel": "quantize_flat_kernel<INT8, F32, SR> on 2^28 elements",
+        line["roofline_quantizer"] = {"bound": "hbm", "kernel": "quantize_flat_f32_kernel<INT8, SR, byte> on 2^28 elements (5 B per element)",
                                       "achieved": qs["int8"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                      "frac": qs["int8"]["frac_of_hbm_peak"], "traffic": None}
+                                      "frac": qs["int8"]["frac_of_hbm_peak"], "traffic": round(TRAFFIC_QUANTIZE_INT8_2P28)}
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(shapes)
     print(json.dumps(line))
