@@ -83,21 +83,79 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
   const uint32_t r0 = (local / tiles_x) * TR, c0 = (local % tiles_x) * TC;
   const uint32_t rows = j.rows, cols = j.cols;
   const size_t n = (size_t)rows * cols;
+  if (j.dtype == SRQ_F32) {
+    // 16 lanes x 16 bytes cover the 64 columns of one tile row: a wave loads 4 rows per
+    // instruction, fully used lines.  A lane holds a quad (half a Philox group) of row rA and
+    // one of row rA + 64; the even lane of a pair draws the block of the first group, the odd
+    // lane the block of the second, and they trade two words (as in quantize_chunk_f32).
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const bool odd = lane & 1u;
+    const uint32_t cq = (lane & 15u) * 4;                    // first column of the quad in the tile
+    const float* x = static_cast<const float*>(j.x);
 #pragma unroll
-  for (int it = 0; it < (TR * TC / 8) / QBLOCK; ++it) {
-    const uint32_t id = it * QBLOCK + threadIdx.x;
-    const uint32_t gc = id % (TC / 8), r = id / (TC / 8);
-    const uint32_t row = r0 + r, col = c0 + gc * 8;
-    uint32_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (row < rows && col < cols) {
-      const size_t g = ((size_t)row * cols + col) / 8;
-      float v[8];
-      job_load_group(v, j, g, n);
-      job_quantize_group<KIND, AS_BF16>(c, v, inv, j, g, k0, k1);
-      if (j.out2) store_group<AS_BF16>(j.out2, g * 8, c);
+    for (int it = 0; it < TR / 32; ++it) {
+      const uint32_t rA = it * 16 + wave * 4 + (lane >> 4), rB = rA + TR / 2;
+      const uint32_t col = c0 + cq;
+      const bool okA = r0 + rA < rows && col < cols, okB = r0 + rB < rows && col < cols;
+      const size_t eA = (size_t)(r0 + rA) * cols + col, eB = (size_t)(r0 + rB) * cols + col;
+      f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+      if (okA) a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x + eA));
+      if (okB) b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x + eB));
+      uint32_t addA[4], addB[4];
+      if (j.round == SRQ_SR) {
+        uint32_t w[4];
+        philox_block(j.counter_offset + (odd ? eB : eA) / 8, k0, k1, w);
+        const uint32_t nb0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[0], 0xB1, 0xF, 0xF, true);
+        const uint32_t nb1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[1], 0xB1, 0xF, 0xF, true);
+        const uint32_t nb2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[2], 0xB1, 0xF, 0xF, true);
+        const uint32_t nb3 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[3], 0xB1, 0xF, 0xF, true);
+        sr_addends(odd ? nb2 : w[0], odd ? nb3 : w[1], addA);
+        sr_addends(odd ? w[2] : nb0, odd ? w[3] : nb1, addB);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) addA[e] = addB[e] = RTN_ADDEND;
+      }
+      uint32_t ca[4], cb[4];
+      if (j.round == SRQ_SR) {
+        quantize_quad<KIND, SRQ_SR, AS_BF16>(ca, a.x, a.y, a.z, a.w, inv, addA);
+        quantize_quad<KIND, SRQ_SR, AS_BF16>(cb, b.x, b.y, b.z, b.w, inv, addB);
+      } else {
+        quantize_quad<KIND, SRQ_RTN, AS_BF16>(ca, a.x, a.y, a.z, a.w, inv, addA);
+        quantize_quad<KIND, SRQ_RTN, AS_BF16>(cb, b.x, b.y, b.z, b.w, inv, addB);
+      }
+      if (j.out2) {
+        if constexpr (AS_BF16) {
+          uint16_t* o = reinterpret_cast<uint16_t*>(j.out2);
+          if (okA) *reinterpret_cast<u32x2*>(o + eA) = u32x2{ca[0] | (ca[1] << 16), ca[2] | (ca[3] << 16)};
+          if (okB) *reinterpret_cast<u32x2*>(o + eB) = u32x2{cb[0] | (cb[1] << 16), cb[2] | (cb[3] << 16)};
+        } else {
+          if (okA) *reinterpret_cast<uint32_t*>(j.out2 + eA) = pack4_bytes(ca);
+          if (okB) *reinterpret_cast<uint32_t*>(j.out2 + eB) = pack4_bytes(cb);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        tile[(cq + e) * PITCH + rA] = (elem_t)(okA ? ca[e] : 0u);
+        tile[(cq + e) * PITCH + rB] = (elem_t)(okB ? cb[e] : 0u);
+      }
     }
+  } else {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) tile[(gc * 8 + e) * PITCH + r] = (elem_t)c[e];
+    for (int it = 0; it < (TR * TC / 8) / QBLOCK; ++it) {
+      const uint32_t id = it * QBLOCK + threadIdx.x;
+      const uint32_t gc = id % (TC / 8), r = id / (TC / 8);
+      const uint32_t row = r0 + r, col = c0 + gc * 8;
+      uint32_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (row < rows && col < cols) {
+        const size_t g = ((size_t)row * cols + col) / 8;
+        float v[8];
+        job_load_group(v, j, g, n);
+        job_quantize_group<KIND, AS_BF16>(c, v, inv, j, g, k0, k1);
+        if (j.out2) store_group<AS_BF16>(j.out2, g * 8, c);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tile[(gc * 8 + e) * PITCH + r] = (elem_t)c[e];
+    }
   }
   __syncthreads();
 #pragma unroll
