@@ -361,11 +361,21 @@ Plan make_plan(size_t P, size_t Q, size_t row_bytes) {
   const size_t ksteps = (row_bytes + BK - 1) / BK;
   size_t nsplit = 1;
   if (t < (size_t)NUM_CU && ksteps >= 16) {
-    nsplit = (NUM_CU + t - 1) / t;               // at least one workgroup per CU
-    const size_t max_split = ksteps / 8;         // keep >= 8 stages per slice
-    if (nsplit > max_split) nsplit = max_split;
-    if (nsplit > 64) nsplit = 64;
-    if (nsplit < 1) nsplit = 1;
+    // Fewer tiles than CUs: cut the contraction into slices.  Cost of a choice, in stages of
+    // one workgroup alone on a CU: the busiest CU runs ceil(t * n / CUs) workgroups of
+    // ceil(stages / n) stages each; two resident workgroups together get about 1.4 times the
+    // rate of one; every slice adds a pass over the output (partial tile out, summed after),
+    // worth about 6 stages.  Keep at least 8 stages per slice.
+    size_t max_split = ksteps / 8;
+    if (max_split > 64) max_split = 64;
+    double best = 0.0;
+    for (size_t n = 1; n <= max_split; ++n) {
+      const size_t per_cu = (t * n + NUM_CU - 1) / NUM_CU;
+      double c = (double)(per_cu * ((ksteps + n - 1) / n));
+      if (per_cu >= 2) c /= 1.4;
+      if (n > 1) c += 6.0 * (double)n;
+      if (n == 1 || c < best) { best = c; nsplit = n; }
+    }
   }
   const size_t steps_per = (ksteps + nsplit - 1) / nsplit;
   pl.k_per_split = (uint32_t)(steps_per * BK);
