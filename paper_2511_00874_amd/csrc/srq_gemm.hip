@@ -139,13 +139,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
   const uint32_t wp = wave / WGN, wq = wave % WGN;
   const uint32_t lds_base = (uint32_t)(size_t)(lds_void*)lds;
   // Workgroup -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each
-  // with its own L2.  XCD x takes the contiguous range of tiles [x * chunk, (x+1) * chunk) in
-  // p-major order and walks it with q fastest: the workgroups that share an X row panel run
-  // side by side on one XCD, and an X panel is fetched from memory by one XCD only.
+  // with its own L2.  XCD x takes the contiguous range [x * chunk, (x+1) * chunk) of a tile
+  // order that walks bands of GROUP tile rows column by column: the workgroups resident on one
+  // XCD at a time (one or two per CU, 32 CUs) then cover a compact block of about GROUP x GROUP
+  // tiles, and share GROUP X row panels and as many Z row panels in that L2 instead of one X
+  // panel and a whole row of Z panels.
+  constexpr uint32_t GROUP = 8;
   const uint32_t ntiles = g.tiles_p * g.tiles_q, chunk = (ntiles + 7u) >> 3;
   const uint32_t tile = (blockIdx.x & 7u) * chunk + (blockIdx.x >> 3);
   if (tile >= ntiles) return;  // padding of the last XCD's range (whole workgroup leaves)
-  const uint32_t tp = tile / g.tiles_q, tq = tile % g.tiles_q;
+  const uint32_t band = tile / (GROUP * g.tiles_q), band_p = band * GROUP;
+  const uint32_t band_rows = min(GROUP, g.tiles_p - band_p), in_band = tile - band * GROUP * g.tiles_q;
+  const uint32_t tp = band_p + in_band % band_rows, tq = in_band / band_rows;
   const uint32_t p0 = tp * BM, q0 = tq * BN;
   const uint32_t kbeg = blockIdx.y * g.k_per_split;
   const uint32_t kend = min(g.R, kbeg + g.k_per_split);
