@@ -144,15 +144,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
   // XCD at a time (one or two per CU, 32 CUs) then cover a compact block of about GROUP x GROUP
   // tiles, and share GROUP X row panels and as many Z row panels in that L2 instead of one X
   // panel and a whole row of Z panels.
+  // With the contraction cut into slices the order is slice-major (all tiles of slice 0, then
+  // slice 1, ...): an XCD then works mostly inside one slice, i.e. on one range of the
+  // contraction of a few panels, instead of on every slice of its tiles.
   constexpr uint32_t GROUP = 8;
-  const uint32_t ntiles = g.tiles_p * g.tiles_q, chunk = (ntiles + 7u) >> 3;
-  const uint32_t tile = (blockIdx.x & 7u) * chunk + (blockIdx.x >> 3);
-  if (tile >= ntiles) return;  // padding of the last XCD's range (whole workgroup leaves)
+  const uint32_t ntiles = g.tiles_p * g.tiles_q, nwork = ntiles * g.nsplit, chunk = (nwork + 7u) >> 3;
+  const uint32_t work = (blockIdx.x & 7u) * chunk + (blockIdx.x >> 3);
+  if (work >= nwork) return;  // padding of the last XCD's range (whole workgroup leaves)
+  const uint32_t slice = work / ntiles, tile = work - slice * ntiles;
   const uint32_t band = tile / (GROUP * g.tiles_q), band_p = band * GROUP;
   const uint32_t band_rows = min(GROUP, g.tiles_p - band_p), in_band = tile - band * GROUP * g.tiles_q;
   const uint32_t tp = band_p + in_band % band_rows, tq = in_band / band_rows;
   const uint32_t p0 = tp * BM, q0 = tq * BN;
-  const uint32_t kbeg = blockIdx.y * g.k_per_split;
+  const uint32_t kbeg = slice * g.k_per_split;
   const uint32_t kend = min(g.R, kbeg + g.k_per_split);
   const int ktiles = (int)((kend - kbeg + BK - 1) / BK);
 
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
   const float s = total_scale(g);
   const bool q_vec = (g.Q & 3u) == 0;
   const uint32_t qw0 = q0 + wq * WTN;
-  uint32_t* const pbase = g.nsplit > 1 ? g.partial + (size_t)blockIdx.y * g.P * g.Q : nullptr;
+  uint32_t* const pbase = g.nsplit > 1 ? g.partial + (size_t)slice * g.P * g.Q : nullptr;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -402,7 +406,7 @@ hipError_t launch_tile(GemmParams g, hipStream_t stream) {
   }
   g.tiles_p = (g.P + BM - 1) / BM;
   g.tiles_q = (g.Q + BN - 1) / BN;
-  dim3 grid(((g.tiles_p * g.tiles_q + 7) / 8) * 8, g.nsplit);
+  dim3 grid(((g.tiles_p * g.tiles_q * g.nsplit + 7) / 8) * 8);
   kern<<<grid, WGM * WGN * 64, LDS_BYTES, stream>>>(g);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
