@@ -42,6 +42,10 @@ _lib.srq_oracle_quantize_one.restype = C.c_uint8
 _lib.srq_oracle_quantize_one.argtypes = [C.c_float, C.c_float, C.c_int, C.c_float]
 _lib.srq_oracle_quantize.argtypes = [_u8p, C.c_void_p, C.c_int, C.c_size_t, C.c_int, C.c_int,
                                      C.c_float, C.c_uint64, C.c_uint64]
+_lib.srq_oracle_sr_bf16_one.restype = C.c_uint16
+_lib.srq_oracle_sr_bf16_one.argtypes = [C.c_float, C.c_float]
+_lib.srq_oracle_update_bf16.argtypes = [C.POINTER(C.c_uint16), _f32p, C.c_float, C.c_size_t, C.c_int,
+                                        C.c_uint64, C.c_uint64]
 _lib.srq_oracle_pack_int4.argtypes = [_u8p, _u8p, C.c_size_t]
 _lib.srq_oracle_unpack_int4.argtypes = [_u8p, _u8p, C.c_size_t]
 _lib.srq_oracle_absmax_scale.restype = C.c_float
@@ -99,6 +103,22 @@ def decode_array(kind: int, codes: np.ndarray) -> np.ndarray:
 
 def quantize_one(x: float, inv: float, kind: int, eps: float) -> int:
     return _lib.srq_oracle_quantize_one(x, inv, kind, eps)
+
+
+def sr_bf16_one(u: float, eps: float) -> int:
+    """Eq. 1 on the bfloat16 grid: bit pattern of Q(u, eps)."""
+    return _lib.srq_oracle_sr_bf16_one(u, eps)
+
+
+def update_bf16(w_bits: np.ndarray, g: np.ndarray, eta: float, seed: int, counter_offset: int,
+                round_mode: int = SR) -> np.ndarray:
+    """Eq. 10: bfloat16 bit patterns of Q_SR(w - eta * g); w_bits is uint16, g float32."""
+    w = np.ascontiguousarray(w_bits, dtype=np.uint16).copy()
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    assert w.size == g.size
+    _lib.srq_oracle_update_bf16(w.ctypes.data_as(C.POINTER(C.c_uint16)), g.ctypes.data_as(_f32p),
+                                float(eta), w.size, round_mode, seed, counter_offset)
+    return w
 
 
 def _src(x: np.ndarray):

@@ -16,6 +16,8 @@
  *     quantized matrices, accumulated in high precision           [Sec. 2.2.2]
  *   - forward  A_out = Q(A) Q(W)                                  [Alg. 1]
  *   - backward dA = Q(dA_out) Q(W)^T, dW = Q(A)^T Q(dA_out)       [Alg. 2]
+ *   - the weight update w <- Q_SR(w - eta * g) onto the bfloat16
+ *     grid                                                         [Eq. 10]
  *
  * Points the paper leaves open (how Delta is chosen, number formats, the
  * random number generator, saturation) are fixed as follows and are the same
@@ -42,12 +44,24 @@
  *     fractional part within 2^-53 of 1, lies above every threshold either
  *     way).  Matrix products are accumulated exactly (int64) or in binary64.
  *
+ *   - the weight update of Eq. 10 takes u = fl32(w - fl32(eta * g)) (two
+ *     binary32 roundings, no fused multiply-add), clamps it to the largest
+ *     finite bfloat16 and applies Eq. 1 on the bfloat16 grid (8 exponent
+ *     bits, 7 fraction bits, subnormals with the spacing of the smallest
+ *     normal binade) with the same thresholds eps = (r16 + 1/2) / 65536: the
+ *     16 random bits face exactly the 16 fraction bits binary32 has beyond
+ *     bfloat16.  NaN gives 0x7FC0, a zero result is +0.
+ *
  * Pins (see tests/test_oracle_*.py): Random123 known-answer vectors for
  * Philox; the worked 0.7 example of Sec. 2.2.1; the closed-form count of
  * thresholds that round up; pass-through of grid points; two-neighbour and
  * error bounds of Lemma 1's proof; unbiasedness and the Bernoulli variance;
  * torch's float8 dtypes for the 8-bit float grids; numpy fp64 matmul for the
- * products; the variance formula in the proof of Lemma 3.
+ * products; the variance formula in the proof of Lemma 3; for the bfloat16
+ * update: pass-through of bfloat16 values, the count of thresholds that round
+ * away from zero (= the 16 dropped bits), exact unbiasedness over all 65536
+ * thresholds, and torch's float32 -> bfloat16 conversion for eps = 1/2 away
+ * from ties.
  * Parity unpinned by the paper: the encodings of NaN/Inf inputs, negative
  * zero and saturation -- these are pinned only by the rules stated here.
  */
@@ -244,6 +258,47 @@ void srq_oracle_quantize(uint8_t* codes, const void* x, int src_dtype, size_t n,
     if (round_mode == ROUND_SR)
       eps = srq_oracle_eps_from_r16(srq_oracle_r16(seed, counter_offset, (uint64_t)i));
     codes[i] = srq_oracle_quantize_one(widen(x, src_dtype, (size_t)i), inv, kind, eps);
+  }
+}
+
+/* Eq. 1 on the bfloat16 grid for one binary32 value u and threshold eps; returns the
+ * bfloat16 bit pattern. */
+uint16_t srq_oracle_sr_bf16_one(float u, float eps) {
+  if (isnan(u)) return 0x7FC0;
+  const float bf16_max = 3.3895313892515355e38f; /* (2 - 2^-7) * 2^127 */
+  if (u > bf16_max) u = bf16_max;
+  if (u < -bf16_max) u = -bf16_max;
+  int e = -126;
+  if (u != 0.0f) {
+    int ex;
+    (void)frexpf(fabsf(u), &ex);
+    e = ex - 1; /* floor(log2 |u|) */
+    if (e < -126) e = -126;
+  }
+  double D = ldexp(1.0, e - 7); /* spacing of the bfloat16 grid at u */
+  double y = (double)u / D;     /* exact; |y| < 2^8 */
+  double fl = floor(y);
+  double frac = y - fl;
+  double qd = (frac < (double)eps) ? fl : fl + 1.0;
+  float v = (float)(qd * D); /* on the bfloat16 grid, hence exact in binary32 */
+  if (v == 0.0f) return 0;
+  uint32_t bits;
+  memcpy(&bits, &v, 4);
+  return (uint16_t)(bits >> 16); /* the low 16 bits are zero */
+}
+
+/* Eq. 10 for a tensor: w[i] <- Q_SR(w[i] - eta * g[i]) on the bfloat16 grid, in place.
+ * Element i uses the same 16-bit slice of the Philox stream as the quantizers. */
+void srq_oracle_update_bf16(uint16_t* w, const float* g, float eta, size_t n, int round_mode,
+                            uint64_t seed, uint64_t counter_offset) {
+#pragma omp parallel for schedule(static)
+  for (long long i = 0; i < (long long)n; ++i) {
+    float eps = 0.5f;
+    if (round_mode == ROUND_SR)
+      eps = srq_oracle_eps_from_r16(srq_oracle_r16(seed, counter_offset, (uint64_t)i));
+    float step = eta * g[i];                       /* one rounding */
+    float u = widen(w, SRC_BF16, (size_t)i) - step; /* one rounding */
+    w[i] = srq_oracle_sr_bf16_one(u, eps);
   }
 }
 
