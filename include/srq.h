@@ -178,6 +178,20 @@ int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void*
                   const srq_quant* qW_bwd, const srq_quant* qA_bwd, float beta, void* workspace,
                   size_t workspace_bytes, void* stream);
 
+/* Weight update of Eq. 10 with the weights stored in bfloat16, in place:
+ *     w[i] <- Q(w[i] - eta * g[i]),   i in [0, n)
+ * Q is the threshold quantizer of Eq. 1 on the bfloat16 grid (8 exponent bits, 7 fraction
+ * bits; subnormals kept), stochastic (round_mode = SRQ_SR: the threshold of element i comes
+ * from 16-bit slice i of the Philox stream (seed, counter_offset), as in sr_quantize) or
+ * nearest with ties toward +inf (SRQ_RTN).  u = w - eta * g is formed in binary32 with one
+ * rounding per operation, clamped to the largest finite bfloat16; NaN gives 0x7FC0; a zero
+ * result is +0.  With g = 0 the weights come back unchanged (-0 becomes +0).
+ * w_bf16: device, n bfloat16 values, read and written; g: device, n floats; both 16-byte
+ * aligned.  eta: host value, finite.  n = 0 is a no-op.  The stream advances by ceil(n / 8)
+ * blocks. */
+int sr_update_bf16(void* w_bf16, const float* g, float eta, size_t n, int round_mode, uint64_t seed,
+                   uint64_t counter_offset, void* stream);
+
 /* Bytes of device scratch the linear entry points need (quantized operands in the layout
  * the product wants, plus split partial sums), for any format.  op: SRQ_OP_*. */
 size_t sr_linear_workspace_bytes(int op, size_t M, size_t N, size_t K);

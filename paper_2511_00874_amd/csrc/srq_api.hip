@@ -373,6 +373,20 @@ int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void*
   return launch_product(dW, dy_t, qdY_bwd, a_t, qA_bwd, N, K, M, pw, beta, gws_w, s);
 }
 
+// Eq. 10 with bfloat16 weights.
+int sr_update_bf16(void* w_bf16, const float* g, float eta, size_t n, int round_mode, uint64_t seed,
+                   uint64_t counter_offset, void* stream) {
+  if (n == 0) return SRQ_OK;
+  if (!w_bf16 || !g) return SRQ_ERR_NULL;
+  if (round_mode != SRQ_SR && round_mode != SRQ_RTN) return SRQ_ERR_FORMAT;
+  if (!(eta == eta) || std::isinf(eta)) return SRQ_ERR_FORMAT;
+  if (!aligned16(w_bf16) || !aligned16(g)) return SRQ_ERR_ALIGN;
+  return launch_update_bf16(static_cast<uint16_t*>(w_bf16), g, eta, n, round_mode, seed, counter_offset,
+                            static_cast<hipStream_t>(stream)) == hipSuccess
+             ? SRQ_OK
+             : SRQ_ERR_HIP;
+}
+
 const char* sr_status_string(int status) {
   switch (status) {
     case SRQ_OK: return "ok";

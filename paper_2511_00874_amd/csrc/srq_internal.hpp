@@ -63,6 +63,11 @@ struct AbsmaxBatch {
 size_t absmax_batch_plan(AbsmaxBatch& b);  // fills first_block / nblocks, returns the block count
 hipError_t launch_absmax_batch(AbsmaxBatch& b, hipStream_t stream);
 
+// Eq. 10 on bfloat16 weights, in place: w[i] <- Q(w[i] - eta * g[i]); element i takes slice i of
+// the Philox stream that starts counter_offset blocks in.
+hipError_t launch_update_bf16(uint16_t* w, const float* g, float eta, size_t n, int round, uint64_t seed,
+                              uint64_t counter_offset, hipStream_t stream);
+
 hipError_t launch_absmax_scale(float* scale_out_dev, const void* x, int dtype, size_t n, int kind,
                                hipStream_t stream);
 

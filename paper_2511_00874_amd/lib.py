@@ -59,15 +59,16 @@ _lib.sr_linear_bwd.argtypes = [_vp, _vp, _vp, C.c_int, _vp, C.c_int, _vp, C.c_in
                                C.c_float, _vp, _sz, _vp]
 _lib.sr_linear_workspace_bytes.argtypes = [C.c_int, _sz, _sz, _sz]
 _lib.sr_linear_workspace_bytes.restype = _sz
+_lib.sr_update_bf16.argtypes = [_vp, _vp, C.c_float, _sz, C.c_int, C.c_uint64, C.c_uint64, _vp]
 _lib.sr_status_string.argtypes = [C.c_int]
 _lib.sr_status_string.restype = C.c_char_p
 for _n in ("sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_linear_fwd", "sr_linear_bwd_data",
-           "sr_linear_bwd_weight", "sr_linear_bwd"):
+           "sr_linear_bwd_weight", "sr_linear_bwd", "sr_update_bf16"):
     getattr(_lib, _n).restype = C.c_int
 
 EXPORTS = ["sr_absmax_scale", "sr_absmax_scales", "sr_absmax_workspace_bytes", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes", "sr_gemm_bf16", "sr_gemm_bf16_workspace_bytes",
            "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight", "sr_linear_bwd",
-           "sr_linear_workspace_bytes", "sr_status_string"]
+           "sr_linear_workspace_bytes", "sr_update_bf16", "sr_status_string"]
 
 raw = _lib  # the C entry points themselves, for tests of the error paths
 
@@ -154,6 +155,14 @@ class AbsmaxBatch:
 def sr_absmax_scales(requests):
     """requests: [(tensor, kind, out 1-element device tensor)]; all scales in two launches."""
     AbsmaxBatch(requests).run()
+
+
+def sr_update_bf16(w, g, eta, seed=0, counter_offset=0, round_mode=SR):
+    """Eq. 10 in place: w (bfloat16 tensor) <- Q(w - eta * g), g float32 of the same size."""
+    assert w.dtype == torch.bfloat16 and g.dtype == torch.float32 and w.numel() == g.numel()
+    assert w.is_contiguous() and g.is_contiguous()
+    _check(_lib.sr_update_bf16(_dev(w), _dev(g), float(eta), w.numel(), round_mode, seed, counter_offset, _stream()))
+    return w
 
 
 def sr_quantize(x, q, transpose_out=False, out=None):

@@ -74,6 +74,16 @@ def test_quantize_argument_checks(lib):
     assert r.sr_quantize(None, None, 0, 0, 8, 0, C.byref(_q(lib)), None) == 0
 
 
+def test_update_argument_checks(lib):
+    import ctypes as C
+    raw = lib.raw
+    assert raw.sr_update_bf16(None, None, 0.1, 0, lib.SR, 0, 0, None) == 0          # empty: no-op
+    assert raw.sr_update_bf16(None, C.c_void_p(256), 0.1, 8, lib.SR, 0, 0, None) == -1
+    assert raw.sr_update_bf16(C.c_void_p(256), C.c_void_p(512), 0.1, 8, 7, 0, 0, None) == -3
+    assert raw.sr_update_bf16(C.c_void_p(256), C.c_void_p(512), float("nan"), 8, lib.SR, 0, 0, None) == -3
+    assert raw.sr_update_bf16(C.c_void_p(258), C.c_void_p(512), 0.1, 8, lib.SR, 0, 0, None) == -4
+
+
 def test_linear_argument_checks(lib):
     r = lib.raw
     buf = 0x1000
