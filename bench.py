@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-quantizer-sweep", action="store_true")
+    ap.add_argument("--train-step", action="store_true",
+                    help="also time whole training steps of the small decoder at batch 8, 32 and 128")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB device copy (known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -132,8 +134,35 @@ def quantizer_sweep(L, synth, torch, reps):
     res["absmax"] = {"ms": round(ms, 4), "GB/s": round(4 * n / (ms * 1e-3) / 1e9, 1),
                      "frac_of_hbm_peak": round(4 * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     del x, out
+    # the weight update of Eq. 10 on 2^28 bfloat16 weights: 2 + 4 bytes read, 2 written per element
+    w = (torch.randn(n, device="cuda:0") * 0.02).to(torch.bfloat16)
+    g = torch.randn(n, device="cuda:0") * 1e-3
+    ms = event_ms(torch, lambda: L.sr_update_bf16(w, g, 1e-3, seed=7, counter_offset=1 << 41), reps)
+    res["update_bf16"] = {"ms": round(ms, 4), "GB/s": round(8 * n / (ms * 1e-3) / 1e9, 1),
+                          "frac_of_hbm_peak": round(8 * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    del w, g
     torch.cuda.empty_cache()
     return res
+
+
+def train_step_times(torch, steps=3):
+    """Whole training step of the 12-layer decoder (d = 768, 12 heads, vocabulary 32000, 1024
+    tokens per sequence, random weights and token ids): forward, backward and the updates, every
+    linear through the SR-quantized path, weights in bfloat16 updated by Eq. 10."""
+    from paper_2511_00874_amd import train
+    model = train.Decoder()
+    out = {"model": "decoder 12 x 768, 12 heads, vocab 32000, seq 1024; %.1f M weights in SR linears"
+                    % (sum(m.in_features * m.out_features for m in model.sr_linears()) / 1e6)}
+    for b, micro in ((8, 1), (32, 1), (128, 4)):
+        ids = torch.randint(0, 32000, (b, 1024), device="cuda:0")
+        tgt = torch.roll(ids, -1, 1)
+        train.train_step(model, ids, tgt, 1e-3, micro)
+        sec = time_steps(torch, lambda: train.train_step(model, ids, tgt, 1e-3, micro), steps, 0)
+        out["b%d" % b] = {"ms_per_step": round(sec * 1e3, 2), "micro_batches": micro,
+                          "sr_linear_TFLOP/s": round(train.flops_per_token(model) * b * 1024 / sec / 1e12, 1)}
+    del model
+    torch.cuda.empty_cache()
+    return out
 
 
 def product_kernel_rooflines(L, torch, layers, reps):
@@ -312,6 +341,8 @@ def main():
         line["roofline_quantizer"] = {"bound": "hbm", "kernel": "quantize_flat_f32_kernel<INT8, SR, byte> on 2^28 elements (5 B per element)",
                                       "achieved": qs["int8"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                       "frac": qs["int8"]["frac_of_hbm_peak"], "traffic": round(TRAFFIC_QUANTIZE_INT8_2P28)}
+    if args.train_step:
+        line["train_step"] = train_step_times(torch)
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)

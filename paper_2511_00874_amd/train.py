@@ -1,0 +1,186 @@
+"""Training with the SR-quantized linear layer: an autograd face of Alg. 1 / Alg. 2 and the
+weight update of Eq. 10, plus a small decoder whose linears all go through it.
+
+Only the linears and the weight update are this library's; embedding, layer norm, attention,
+GELU and the loss are plain PyTorch operators (they are not quantized in the paper's method,
+Sec. 3.1: the quantization sites are the inputs of the matrix products).
+"""
+import torch
+import torch.nn.functional as F
+
+from . import lib as L
+
+# Rows per call: keeps every operand matrix of the products below the library's 2 GiB limit for
+# the widest layer used here (32000 outputs in the two-byte form).  Token chunks are independent
+# in Y and dA; dW accumulates over them (beta = 1), which is also how micro-batches accumulate.
+MAX_ROWS = 16384
+
+
+class SRLinearFn(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, layer):
+        ctx.layer = layer
+        ctx.shape = x.shape
+        a = x.reshape(-1, x.shape[-1]).contiguous().float()
+        ctx.save_for_backward(a)
+        return layer._forward(a).reshape(*x.shape[:-1], layer.out_features)
+
+    @staticmethod
+    def backward(ctx, dy):
+        (a,) = ctx.saved_tensors
+        layer = ctx.layer
+        da = layer._backward(dy.reshape(-1, layer.out_features).contiguous().float(), a)
+        return da.reshape(ctx.shape), None
+
+
+class SRLinear(torch.nn.Module):
+    """y = Q(x) Q(W)^T with the five quantizers of Alg. 1 / Alg. 2 (per-tensor absmax scales,
+    fresh stream positions every call); W is held in bfloat16 and updated by Eq. 10.
+
+    The weight gradient is kept by the layer (`self.dW`, float32, accumulated over backward
+    calls until `update`), not handed to autograd: the update consumes it in place."""
+
+    def __init__(self, in_features, out_features, seed, fwd_kind=L.INT8, bwd_kind=L.E5M2, device="cuda:0",
+                 init_std=0.02, round_mode=L.SR):
+        super().__init__()
+        self.in_features, self.out_features = in_features, out_features
+        g = torch.Generator(device=device).manual_seed(seed)
+        w = torch.randn((out_features, in_features), device=device, generator=g) * init_std
+        self.weight = w.to(torch.bfloat16)           # not an nn.Parameter: autograd never sees it
+        self.dW = torch.zeros((out_features, in_features), dtype=torch.float32, device=device)
+        self.have_grad = False
+        self.kinds = {"A_fwd": fwd_kind, "W_fwd": fwd_kind, "A_bwd": bwd_kind, "W_bwd": bwd_kind, "dY_bwd": bwd_kind}
+        self.scales = torch.ones(5, dtype=torch.float32, device=device)
+        self.seed, self.position, self.round_mode = seed, 0, round_mode
+        self.ws = None
+
+    def _q(self, name, slot, position):
+        return L.Quant(self.kinds[name], self.scales[slot:slot + 1], seed=self.seed, counter_offset=position,
+                       round_mode=self.round_mode)
+
+    def _workspace(self, op, M):
+        need = L.sr_linear_workspace_bytes(op, M, self.out_features, self.in_features)
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.empty(need, dtype=torch.uint8, device=self.weight.device)
+        return self.ws
+
+    def _forward(self, a):
+        M, K = a.shape
+        N = self.out_features
+        w = self.weight
+        L.sr_absmax_scales([(a, self.kinds["A_fwd"], self.scales[0:1]), (w, self.kinds["W_fwd"], self.scales[1:2]),
+                            (a, self.kinds["A_bwd"], self.scales[2:3]), (w, self.kinds["W_bwd"], self.scales[3:4])])
+        # every tensor gets its own stretch of the stream (in blocks of 8 elements); a chunk that
+        # starts at row r0 continues where the rows before it would have drawn, so the codes do
+        # not depend on the chunking.  The backward quantizers of A and W get theirs now.
+        a_blocks, w_blocks = (M * K + 7) // 8, (N * K + 7) // 8
+        pos_w, pos_a = self.position, self.position + w_blocks
+        self._bwd_pos = (pos_a + a_blocks, pos_a + 2 * a_blocks)
+        self.position = pos_a + 2 * a_blocks + w_blocks
+        y = torch.empty((M, N), dtype=torch.float32, device=a.device)
+        qw = self._q("W_fwd", 1, pos_w)
+        for r0 in range(0, M, MAX_ROWS):
+            r1 = min(M, r0 + MAX_ROWS)
+            L.sr_linear_fwd(a[r0:r1], w, self._q("A_fwd", 0, pos_a + (r0 * K) // 8), qw, out=y[r0:r1],
+                            workspace=self._workspace(L.OP_FWD, r1 - r0))
+        return y
+
+    def _backward(self, dy, a):
+        M, N = dy.shape
+        K = self.in_features
+        w = self.weight
+        L.sr_absmax_scales([(dy, self.kinds["dY_bwd"], self.scales[4:5])])
+        da = torch.empty((M, K), dtype=torch.float32, device=dy.device)
+        pos_a, pos_w = self._bwd_pos
+        pos_dy = self.position
+        self.position += (M * N + 7) // 8
+        qw = self._q("W_bwd", 3, pos_w)
+        for r0 in range(0, M, MAX_ROWS):
+            r1 = min(M, r0 + MAX_ROWS)
+            L.sr_linear_bwd(dy[r0:r1], w, a[r0:r1], self._q("dY_bwd", 4, pos_dy + (r0 * N) // 8), qw,
+                            self._q("A_bwd", 2, pos_a + (r0 * K) // 8), out_dA=da[r0:r1], out_dW=self.dW,
+                            beta=1.0 if self.have_grad else 0.0, workspace=self._workspace(L.OP_BWD, r1 - r0))
+            self.have_grad = True
+        return da
+
+    def forward(self, x):
+        return SRLinearFn.apply(x, self)
+
+    def update(self, lr):
+        """Eq. 10: W <- Q_SR(W - lr * dW) on the bfloat16 grid; clears the accumulated gradient."""
+        if self.have_grad:
+            L.sr_update_bf16(self.weight.view(-1), self.dW.view(-1), lr, seed=self.seed, counter_offset=self.position,
+                             round_mode=self.round_mode)
+            self.position += (self.weight.numel() + 7) // 8
+            self.have_grad = False
+
+
+class Block(torch.nn.Module):
+    def __init__(self, d, heads, seed, device):
+        super().__init__()
+        self.heads = heads
+        self.ln1 = torch.nn.LayerNorm(d, device=device)
+        self.ln2 = torch.nn.LayerNorm(d, device=device)
+        self.qkv = SRLinear(d, 3 * d, seed, device=device)
+        self.proj = SRLinear(d, d, seed + 1, device=device)
+        self.fc1 = SRLinear(d, 4 * d, seed + 2, device=device)
+        self.fc2 = SRLinear(4 * d, d, seed + 3, device=device)
+
+    def forward(self, x):
+        B, T, d = x.shape
+        q, k, v = self.qkv(self.ln1(x)).view(B, T, 3, self.heads, d // self.heads).permute(2, 0, 3, 1, 4)
+        att = F.scaled_dot_product_attention(q.bfloat16(), k.bfloat16(), v.bfloat16(), is_causal=True).float()
+        x = x + self.proj(att.transpose(1, 2).reshape(B, T, d))
+        return x + self.fc2(F.gelu(self.fc1(self.ln2(x))))
+
+
+class Decoder(torch.nn.Module):
+    """Pre-norm decoder: token + position embedding, `layers` blocks, final norm, output head."""
+
+    def __init__(self, vocab=32000, d=768, heads=12, layers=12, seq=1024, seed=1, device="cuda:0"):
+        super().__init__()
+        self.tok = torch.nn.Embedding(vocab, d, device=device)
+        self.pos = torch.nn.Embedding(seq, d, device=device)
+        torch.nn.init.normal_(self.tok.weight, std=0.02)
+        torch.nn.init.normal_(self.pos.weight, std=0.02)
+        self.blocks = torch.nn.ModuleList([Block(d, heads, seed + 10 * i, device) for i in range(layers)])
+        self.ln = torch.nn.LayerNorm(d, device=device)
+        self.head = SRLinear(d, vocab, seed + 10 * layers, device=device)
+
+    def sr_linears(self):
+        return [m for m in self.modules() if isinstance(m, SRLinear)]
+
+    def forward(self, ids):
+        B, T = ids.shape
+        x = self.tok(ids) + self.pos(torch.arange(T, device=ids.device))
+        for blk in self.blocks:
+            x = blk(x)
+        return self.head(self.ln(x))
+
+
+def train_step(model, ids, targets, lr, micro_batches=1):
+    """One mini-batch step: forward and backward over `micro_batches` slices of the batch (weight
+    gradients accumulate inside the SR linears, the others in .grad), then the updates: Eq. 10 for
+    the SR linears, plain SGD for the float32 parameters.  Returns the mean loss (device tensor)."""
+    total = None
+    for ids_mb, tgt_mb in zip(ids.chunk(micro_batches), targets.chunk(micro_batches)):
+        logits = model(ids_mb)
+        loss = F.cross_entropy(logits.view(-1, logits.shape[-1]), tgt_mb.reshape(-1)) / micro_batches
+        loss.backward()
+        total = loss.detach() if total is None else total + loss.detach()
+    for m in model.sr_linears():
+        m.update(lr)
+    with torch.no_grad():
+        for p in model.parameters():
+            if p.grad is not None:
+                p.add_(p.grad, alpha=-lr)
+                p.grad = None
+    return total
+
+
+def flops_per_token(model):
+    """6 x (parameters of the SR linears): forward + the two backward products."""
+    return 6.0 * sum(m.in_features * m.out_features for m in model.sr_linears())
+
+
+__all__ = ["SRLinear", "Decoder", "train_step", "flops_per_token", "MAX_ROWS"]
