@@ -13,10 +13,10 @@ import numpy as np
 
 from . import build as _build
 
-NONE, INT8, INT4, E4M3, E5M2 = 0, 1, 2, 3, 4
+NONE, INT8, INT4, E4M3, E5M2, E4M2, E4M1, E4M0 = 0, 1, 2, 3, 4, 5, 6, 7
 SR, RTN = 0, 1
 F32, BF16 = 0, 1
-KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2"}
+KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2", E4M2: "e4m2", E4M1: "e4m1", E4M0: "e4m0"}
 
 _lib = C.CDLL(_build.build(force=False))
 

@@ -73,7 +73,8 @@
 #include <omp.h>
 #endif
 
-enum { KIND_NONE = 0, KIND_INT8 = 1, KIND_INT4 = 2, KIND_E4M3 = 3, KIND_E5M2 = 4 };
+enum { KIND_NONE = 0, KIND_INT8 = 1, KIND_INT4 = 2, KIND_E4M3 = 3, KIND_E5M2 = 4,
+       KIND_E4M2 = 5, KIND_E4M1 = 6, KIND_E4M0 = 7 };
 enum { ROUND_SR = 0, ROUND_RTN = 1 };
 enum { SRC_F32 = 0, SRC_BF16 = 1 };
 
@@ -149,9 +150,23 @@ float srq_oracle_eps_from_r16(uint32_t r16) {
 /* ------------------------------------------------------------------ */
 /* Formats.                                                             */
 /* ------------------------------------------------------------------ */
-static int kind_is_float(int kind) { return kind == KIND_E4M3 || kind == KIND_E5M2; }
-static int kind_mbits(int kind) { return kind == KIND_E4M3 ? 3 : 2; }
-static int kind_bias(int kind) { return kind == KIND_E4M3 ? 7 : 15; }
+/* E4M2 / E4M1 / E4M0 (the 4-exponent-bit formats of the paper's experiments, Sec. 5): the
+ * paper does not state their bias or subnormal rule; they are read here as sub-grids of
+ * E4M3 -- same exponent range (bias 7, subnormals at the spacing of the smallest normal
+ * binade), 2 / 1 / 0 fraction bits -- and their codes are stored as the E4M3 code of the
+ * same value (the low 1 / 2 / 3 fraction bits zero). */
+static int kind_is_float(int kind) { return kind >= KIND_E4M3 && kind <= KIND_E4M0; }
+static int kind_mbits(int kind) {
+  switch (kind) {
+    case KIND_E4M3: return 3;
+    case KIND_E4M1: return 1;
+    case KIND_E4M0: return 0;
+    default: return 2; /* E5M2, E4M2 */
+  }
+}
+static int kind_bias(int kind) { return kind == KIND_E5M2 ? 15 : 7; }
+/* the format whose byte encoding the codes use */
+static int kind_storage(int kind) { return kind >= KIND_E4M2 && kind <= KIND_E4M0 ? KIND_E4M3 : kind; }
 
 float srq_oracle_qmax(int kind) {
   switch (kind) {
@@ -159,6 +174,9 @@ float srq_oracle_qmax(int kind) {
     case KIND_INT4: return 7.0f;
     case KIND_E4M3: return 448.0f;   /* 1.75 * 2^8  */
     case KIND_E5M2: return 57344.0f; /* 1.75 * 2^15 */
+    case KIND_E4M2: return 448.0f;   /* 1.75 * 2^8: the E4M3 maximum has only two fraction bits set */
+    case KIND_E4M1: return 384.0f;   /* 1.5  * 2^8  */
+    case KIND_E4M0: return 256.0f;   /* 2^8         */
     default: return 0.0f;
   }
 }
@@ -170,6 +188,7 @@ float srq_oracle_qmax(int kind) {
  * infinities and a single NaN mantissa pattern (all ones), E5M2 is IEEE-like. */
 double srq_oracle_decode(int kind, uint8_t code) {
   if (!kind_is_float(kind)) return (double)(int8_t)code;
+  kind = kind_storage(kind);
   int m = kind_mbits(kind), bias = kind_bias(kind);
   int sign = code >> 7;
   int efield = (code & 0x7F) >> m;
@@ -192,6 +211,7 @@ double srq_oracle_decode(int kind, uint8_t code) {
 static uint8_t encode_on_grid(int kind, float v) {
   if (!kind_is_float(kind)) return (uint8_t)(int8_t)(int)v;
   if (v == 0.0f) return 0; /* +0 also for results that came from negatives */
+  kind = kind_storage(kind);
   int m = kind_mbits(kind), bias = kind_bias(kind);
   int sign = v < 0.0f;
   float a = fabsf(v);

@@ -13,10 +13,13 @@ import pytest
 import torch
 
 import oracle
-from oracle import E4M3, E5M2, INT4, INT8, RTN, SR
+from oracle import E4M0, E4M1, E4M2, E4M3, E5M2, INT4, INT8, RTN, SR
 
-KINDS = [INT8, INT4, E4M3, E5M2]
-FKINDS = {E4M3: (3, -6, torch.float8_e4m3fn), E5M2: (2, -14, torch.float8_e5m2)}
+KINDS = [INT8, INT4, E4M3, E5M2, E4M2, E4M1, E4M0]
+# fraction bits, smallest normal exponent, torch dtype whose byte encoding the codes use
+FKINDS = {E4M3: (3, -6, torch.float8_e4m3fn), E5M2: (2, -14, torch.float8_e5m2),
+          E4M2: (2, -6, torch.float8_e4m3fn), E4M1: (1, -6, torch.float8_e4m3fn), E4M0: (0, -6, torch.float8_e4m3fn)}
+SUBGRID_ZERO_BITS = {E4M2: 1, E4M1: 2, E4M0: 3}  # stored as E4M3 codes with these low fraction bits zero
 ALL_R16 = np.arange(65536)
 EPS = np.array([oracle.eps_from_r16(int(r)) for r in ALL_R16], dtype=np.float32)
 
@@ -181,6 +184,10 @@ def test_grid_points_pass_through_for_every_threshold(kind):
         codes = [c for c in codes if oracle.decode(kind, c) >= -127]
     if kind == INT4:
         codes = [c for c in codes if abs(oracle.decode(kind, c)) <= 7]
+    if kind in SUBGRID_ZERO_BITS:
+        low = (1 << SUBGRID_ZERO_BITS[kind]) - 1
+        codes = [c for c in codes if (c & low) == 0 and abs(oracle.decode(kind, c)) <= oracle.qmax(kind)]
+        assert len(codes) == {E4M2: 128, E4M1: 64, E4M0: 32}[kind]  # every such E4M3 code is finite and in range
     scale = 0.5  # exact arithmetic: value = grid * 0.5
     for c in codes:
         v = oracle.decode(kind, c)
@@ -305,6 +312,29 @@ def test_max_codes_are_the_published_ones():
     assert oracle.quantize_one(-1.0, 1.0, E4M3, 0.5) == 0xB8
     assert oracle.quantize_one(-1.0, 1.0, E5M2, 0.5) == 0xBC
     assert oracle.quantize_one(-127.0, 1.0, INT8, 0.5) == 0x81
+
+
+def test_sub_grids_of_e4m3():
+    # E4M2 / E4M1 / E4M0: same exponent range as E4M3, fewer fraction bits, stored as E4M3 codes
+    assert oracle.quantize_one(448.0, 1.0, E4M2, 0.5) == 0x7E and oracle.qmax(E4M2) == 448.0
+    assert oracle.quantize_one(1e9, 1.0, E4M1, 0.5) == 0x7C and oracle.qmax(E4M1) == 384.0
+    assert oracle.quantize_one(1e9, 1.0, E4M0, 0.5) == 0x78 and oracle.qmax(E4M0) == 256.0
+    assert oracle.quantize_one(2.0**-8, 1.0, E4M2, 0.5) == 0x02   # smallest subnormal: half the E4M3 resolution
+    assert oracle.quantize_one(2.0**-7, 1.0, E4M1, 0.5) == 0x04
+    assert oracle.quantize_one(2.0**-6, 1.0, E4M0, 0.5) == 0x08   # no subnormals but zero
+    assert oracle.quantize_one(2.0**-7 * 0.99, 1.0, E4M0, 0.5) == 0x00 and oracle.quantize_one(2.0**-7, 1.0, E4M0, 0.5) == 0x08
+    # 1.3 lies between 1.25 and 1.5 (E4M2), 1.0 and 1.5 (E4M1), 1.0 and 2.0 (E4M0)
+    for kind, lo, hi in ((E4M2, 1.25, 1.5), (E4M1, 1.0, 1.5), (E4M0, 1.0, 2.0)):
+        assert oracle.decode(kind, oracle.quantize_one(1.3, 1.0, kind, oracle.eps_from_r16(65535))) == lo
+        assert oracle.decode(kind, oracle.quantize_one(1.3, 1.0, kind, oracle.eps_from_r16(0))) == hi
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(50000) * 40).astype(np.float32)
+    e4m3_values = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()
+    for kind, zero_bits in SUBGRID_ZERO_BITS.items():
+        codes = oracle.quantize(x, kind, 1.0, 3, 0)
+        assert np.all(codes & ((1 << zero_bits) - 1) == 0)
+        assert np.all(np.abs(e4m3_values[codes]) <= oracle.qmax(kind))
+        assert np.array_equal(e4m3_values[codes].astype(np.float64), oracle.decode_array(kind, codes))
 
 
 # ---- int4 storage ------------------------------------------------------------------------
