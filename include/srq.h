@@ -65,7 +65,15 @@ typedef enum { SRQ_F32 = 0, SRQ_BF16 = 1 } srq_dtype; /* dtype of a source tenso
  * in bits 3:0 and 2k+1 in bits 7:4 of byte k (pairs run along the contiguous dimension of
  * the output).  E4M3 / E5M2: OCP 8-bit floats (bias 7 / 15, subnormals, max 448 / 57344;
  * never Inf, NaN only from NaN input).  Any zero result is stored as +0. */
-typedef enum { SRQ_NONE = 0, SRQ_INT8 = 1, SRQ_INT4 = 2, SRQ_E4M3 = 3, SRQ_E5M2 = 4 } srq_kind;
+typedef enum {
+  SRQ_NONE = 0, SRQ_INT8 = 1, SRQ_INT4 = 2, SRQ_E4M3 = 3, SRQ_E5M2 = 4,
+  /* The 4-exponent-bit formats of the paper's experiments (Sec. 5) with 2 / 1 / 0 fraction bits.
+   * The paper does not give their bias or subnormal rule; here they are the sub-grids of E4M3
+   * with the same exponent range (subnormals at the spacing of the smallest normal binade),
+   * Qmax 448 / 384 / 256, and their codes are the E4M3 codes of the same values (low 1 / 2 / 3
+   * fraction bits zero), so that products treat them as E4M3. */
+  SRQ_E4M2 = 5, SRQ_E4M1 = 6, SRQ_E4M0 = 7
+} srq_kind;
 
 typedef enum { SRQ_SR = 0, SRQ_RTN = 1 } srq_round; /* Def. 3 / Def. 2 */
 

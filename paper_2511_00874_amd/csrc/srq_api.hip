@@ -13,7 +13,7 @@ constexpr size_t WS_ALIGN = 256;
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-bool kind_ok(int k) { return k == SRQ_INT8 || k == SRQ_INT4 || k == SRQ_E4M3 || k == SRQ_E5M2; }
+bool kind_ok(int k) { return k >= SRQ_INT8 && k <= SRQ_E4M0; }
 bool dtype_ok(int d) { return d == SRQ_F32 || d == SRQ_BF16; }
 
 int check_quant(const srq_quant* q) {

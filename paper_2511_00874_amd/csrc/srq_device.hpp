@@ -74,11 +74,21 @@ template <> struct Grid<SRQ_E5M2> {
   static constexpr bool is_float = true; static constexpr float qmax = 57344.0f;
   static constexpr int mbits = 2, emin = -14;
 };
+// E4M2 / E4M1 / E4M0: sub-grids of E4M3 whose fraction width and Qmax are run-time values (one
+// instantiation serves the three); codes are written as E4M3 codes.
+constexpr int SRQ_E4MX = 100;
+template <> struct Grid<SRQ_E4MX> {
+  static constexpr bool is_float = true; static constexpr float qmax = 0.0f;  // unused: InvScale::sub_qmax
+  static constexpr int mbits = 0, emin = -6;                                  // mbits unused: InvScale::sub_m
+};
+__host__ __device__ constexpr bool kind_is_e4mx(int kind) { return kind >= SRQ_E4M2 && kind <= SRQ_E4M0; }
 
 // Per-tensor constants of the multiply that produces the grid coordinate.
 struct InvScale {
   float inv;    // fl32(1 / scale)
   float inv16;  // inv * 2^16 (exact): fl32(x * inv16) = fl32(x * inv) * 2^16
+  int sub_m;        // SRQ_E4MX only: fraction bits (2, 1, 0)
+  float sub_qmax;   // SRQ_E4MX only: 448, 384, 256
 };
 
 // One element through Eq. 1 on grid KIND.  Returns the code in the low 8 bits (integers:
@@ -102,23 +112,26 @@ __device__ __forceinline__ uint32_t quantize_elem(float x, const InvScale& s, ui
     code = (uint32_t)q;
     if (FIX_NAN && x != x) code = 0u;
   } else {
+    const int m = KIND == SRQ_E4MX ? s.sub_m : G::mbits;
+    const float qm = KIND == SRQ_E4MX ? s.sub_qmax : G::qmax;
     float t = __fmul_rn(x, s.inv);                                      // grid coordinate
-    t = __builtin_amdgcn_fmed3f(t, -G::qmax, G::qmax);                  // saturate (NaN fixed up below)
+    t = __builtin_amdgcn_fmed3f(t, -qm, qm);                            // saturate (NaN fixed up below)
     // spacing of the grid at t: D = 2^(e - m), e = max(floor(log2|t|), emin)
     const uint32_t a = __float_as_uint(t) & 0x7FFFFFFFu;
     const int eb = max((int)(a >> 23), G::emin + 127);                  // biased e (0 and subnormals clamp)
-    const float up16 = __uint_as_float((uint32_t)(270 + G::mbits - eb) << 23);  // 2^(16 + m - e)
+    const float up16 = __uint_as_float((uint32_t)(270 + m - eb) << 23);  // 2^(16 + m - e)
     const float y16 = __fmul_rn(t, up16);                               // (t / D) * 2^16, exact
     const int u = ROUND == SRQ_SR ? cvt_rpi(y16) : cvt_flr(y16);
     const int q = (u + (int)addend) >> 16;                              // |q| in [0, 2^(m+1)]
     if constexpr (AS_BF16) {
-      const float d = __uint_as_float((uint32_t)(eb - G::mbits) << 23);  // D = 2^(e - m)
+      const float d = __uint_as_float((uint32_t)(eb - m) << 23);        // D = 2^(e - m)
       code = __float_as_uint(__fmul_rn((float)q, d)) >> 16;             // exact, <= 4 significant bits
       if (FIX_NAN && x != x) code = 0x7FC0u;
     } else {
       // sign | ((e - emin) << m) + |q| : covers subnormals (field 0), normals (the hidden one
       // of |q| bumps the field) and the carry into the next binade
-      const uint32_t mag = ((uint32_t)(eb - (G::emin + 127)) << G::mbits) + (uint32_t)abs(q);
+      uint32_t mag = ((uint32_t)(eb - (G::emin + 127)) << m) + (uint32_t)abs(q);
+      if constexpr (KIND == SRQ_E4MX) mag <<= 3 - m;                    // the E4M3 code of the same value
       code = mag | (q < 0 ? 0x80u : 0u);
       if (FIX_NAN && x != x) code = 0x7Fu;
     }
@@ -158,11 +171,14 @@ __device__ __forceinline__ uint32_t pack4_nibbles(const uint32_t (&c)[4]) {
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
 // 1 / scale, correctly rounded, from a host value or a device-resident one.
-__device__ __forceinline__ InvScale inv_scale(float scale, const float* scale_dev) {
+// `kind` is the srq_kind of the tensor (it fills the run-time grid parameters of SRQ_E4MX).
+__device__ __forceinline__ InvScale inv_scale(float scale, const float* scale_dev, int kind) {
   const float sc = scale_dev ? *scale_dev : scale;
   InvScale s;
   s.inv = __fdiv_rn(1.0f, sc);
   s.inv16 = __fmul_rn(s.inv, 65536.0f);
+  s.sub_m = SRQ_E4M0 - kind;  // E4M2 -> 2, E4M1 -> 1, E4M0 -> 0
+  s.sub_qmax = kind == SRQ_E4M2 ? 448.0f : kind == SRQ_E4M1 ? 384.0f : 256.0f;
   return s;
 }
 

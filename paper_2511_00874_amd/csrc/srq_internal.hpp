@@ -96,6 +96,7 @@ hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint
                              bool accumulate, void* workspace, hipStream_t stream);
 
 inline bool kind_is_int(int k) { return k == SRQ_INT8 || k == SRQ_INT4; }
-inline bool kind_is_f8(int k) { return k == SRQ_E4M3 || k == SRQ_E5M2; }
+// 8-bit float codes: E4M3, E5M2 and the sub-grids of E4M3 (stored as E4M3 codes)
+inline bool kind_is_f8(int k) { return k >= SRQ_E4M3 && k <= SRQ_E4M0; }
 
 }  // namespace srq

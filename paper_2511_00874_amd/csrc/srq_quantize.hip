@@ -26,9 +26,9 @@ __device__ __forceinline__ uint32_t pack_nibbles(const uint32_t (&c)[8]) {
 template <int KIND, int SRC, int ROUND, int STORE>
 __global__ __launch_bounds__(QBLOCK) void quantize_flat_kernel(uint8_t* __restrict__ out,
                                                                const void* __restrict__ x, size_t n,
-                                                               float scale, const float* scale_dev,
+                                                               float scale, const float* scale_dev, int kind,
                                                                uint64_t seed, uint64_t counter_offset) {
-  const InvScale inv = inv_scale(scale, scale_dev);
+  const InvScale inv = inv_scale(scale, scale_dev, kind);
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
   const size_t ngroups = (n + 7) / 8;
   const size_t stride = (size_t)gridDim.x * QBLOCK;
@@ -73,9 +73,9 @@ __global__ __launch_bounds__(QBLOCK) void quantize_flat_kernel(uint8_t* __restri
 template <int KIND, int ROUND, int STORE>
 __global__ __launch_bounds__(QBLOCK) void quantize_flat_f32_kernel(uint8_t* __restrict__ out,
                                                                    const float* __restrict__ x, size_t nchunks,
-                                                                   float scale, const float* scale_dev,
+                                                                   float scale, const float* scale_dev, int kind,
                                                                    uint64_t seed, uint64_t counter_offset) {
-  const InvScale inv = inv_scale(scale, scale_dev);
+  const InvScale inv = inv_scale(scale, scale_dev, kind);
   const uint32_t lane = threadIdx.x & 63u;
   const size_t waves = (size_t)gridDim.x * (QBLOCK / 64);
   for (size_t c = (size_t)blockIdx.x * (QBLOCK / 64) + (threadIdx.x >> 6); c < nchunks; c += waves)
@@ -92,13 +92,13 @@ constexpr int TR = 128, TC = 64;
 template <int KIND, int SRC, int ROUND, int STORE>
 __global__ __launch_bounds__(QBLOCK) void quantize_transpose_kernel(
     uint8_t* __restrict__ out, const void* __restrict__ x, uint32_t rows, uint32_t cols, float scale,
-    const float* scale_dev, uint64_t seed, uint64_t counter_offset) {
+    const float* scale_dev, int kind, uint64_t seed, uint64_t counter_offset) {
   // one tile element per code: a byte, or 16 bits when the grid values are stored as bfloat16
   using elem_t = typename std::conditional<STORE == STORE_BF16, uint16_t, uint8_t>::type;
   constexpr int ES = sizeof(elem_t);
   constexpr int PITCH = TR + 4 / ES;            // elements; keeps rows 4-byte aligned
   __shared__ __attribute__((aligned(16))) elem_t tile[TC * PITCH];
-  const InvScale inv = inv_scale(scale, scale_dev);
+  const InvScale inv = inv_scale(scale, scale_dev, kind);
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
   const uint32_t r0 = blockIdx.y * TR, c0 = blockIdx.x * TC;
   const size_t n = (size_t)rows * cols;
@@ -292,7 +292,9 @@ float qmax_of(int kind) {
   switch (kind) {
     case SRQ_INT8: return 127.0f;
     case SRQ_INT4: return 7.0f;
-    case SRQ_E4M3: return 448.0f;
+    case SRQ_E4M3: case SRQ_E4M2: return 448.0f;
+    case SRQ_E4M1: return 384.0f;
+    case SRQ_E4M0: return 256.0f;
     default: return 57344.0f;
   }
 }
@@ -303,7 +305,7 @@ hipError_t launch_one(void* codes, const void* x, size_t rows, size_t cols, int 
   if (transpose_out) {
     dim3 grid((unsigned)((cols + TC - 1) / TC), (unsigned)((rows + TR - 1) / TR));
     quantize_transpose_kernel<KIND, SRC, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
-        static_cast<uint8_t*>(codes), x, (uint32_t)rows, (uint32_t)cols, a.scale, a.scale_dev, a.seed,
+        static_cast<uint8_t*>(codes), x, (uint32_t)rows, (uint32_t)cols, a.scale, a.scale_dev, a.kind, a.seed,
         a.counter_offset);
   } else {
     const size_t n = rows * cols;
@@ -313,7 +315,7 @@ hipError_t launch_one(void* codes, const void* x, size_t rows, size_t cols, int 
       if (nchunks > 0) {
         const int grid = grid_for(nchunks, QBLOCK / 64, 1 << 22);
         quantize_flat_f32_kernel<KIND, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
-            static_cast<uint8_t*>(codes), static_cast<const float*>(x), nchunks, a.scale, a.scale_dev, a.seed,
+            static_cast<uint8_t*>(codes), static_cast<const float*>(x), nchunks, a.scale, a.scale_dev, a.kind, a.seed,
             a.counter_offset);
         done = nchunks * CHUNK;
       }
@@ -325,7 +327,7 @@ hipError_t launch_one(void* codes, const void* x, size_t rows, size_t cols, int 
       const int grid = grid_for((n - done + 7) / 8, QBLOCK * 4, 1 << 20);
       quantize_flat_kernel<KIND, SRC, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
           static_cast<uint8_t*>(codes) + out_bytes, static_cast<const uint8_t*>(x) + done * es, n - done, a.scale,
-          a.scale_dev, a.seed, a.counter_offset + done / 8);
+          a.scale_dev, a.kind, a.seed, a.counter_offset + done / 8);
     }
   }
   return hipGetLastError();
@@ -361,6 +363,10 @@ hipError_t launch_quantize(void* codes, const void* x, size_t rows, size_t cols,
       return a.store == STORE_BF16
                  ? dispatch_src_round<SRQ_E5M2, STORE_BF16>(codes, x, rows, cols, transpose_out, a, stream)
                  : dispatch_src_round<SRQ_E5M2, STORE_BYTE>(codes, x, rows, cols, transpose_out, a, stream);
+    case SRQ_E4M2: case SRQ_E4M1: case SRQ_E4M0:
+      return a.store == STORE_BF16
+                 ? dispatch_src_round<SRQ_E4MX, STORE_BF16>(codes, x, rows, cols, transpose_out, a, stream)
+                 : dispatch_src_round<SRQ_E4MX, STORE_BYTE>(codes, x, rows, cols, transpose_out, a, stream);
     default: return hipErrorInvalidValue;
   }
 }

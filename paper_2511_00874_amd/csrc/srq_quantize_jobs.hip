@@ -46,7 +46,7 @@ __device__ __forceinline__ void store_group(uint8_t* out, size_t base, const uin
 // what is left over, and bfloat16 sources, group-wise.
 template <int KIND, bool AS_BF16>
 __device__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
-  const InvScale inv = inv_scale(j.scale, j.scale_dev);
+  const InvScale inv = inv_scale(j.scale, j.scale_dev, j.kind);
   const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
   const size_t n = (size_t)j.rows * j.cols, ngroups = n / 8;
   size_t first_group = 0;
@@ -77,7 +77,7 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
   constexpr int ES = sizeof(elem_t);
   constexpr int PITCH = TR + 4 / ES;
   elem_t* tile = reinterpret_cast<elem_t*>(smem);
-  const InvScale inv = inv_scale(j.scale, j.scale_dev);
+  const InvScale inv = inv_scale(j.scale, j.scale_dev, j.kind);
   const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
   const uint32_t tiles_x = (j.cols + TC - 1) / TC;
   const uint32_t r0 = (local / tiles_x) * TR, c0 = (local % tiles_x) * TC;
@@ -194,9 +194,13 @@ __global__ __launch_bounds__(QBLOCK) void quantize_jobs_kernel(QuantJobs jobs) {
       if (bf) run_job<SRQ_E4M3, true>(j, local, smem);
       else run_job<SRQ_E4M3, false>(j, local, smem);
       break;
-    default:
+    case SRQ_E5M2:
       if (bf) run_job<SRQ_E5M2, true>(j, local, smem);
       else run_job<SRQ_E5M2, false>(j, local, smem);
+      break;
+    default:  // E4M2 / E4M1 / E4M0
+      if (bf) run_job<SRQ_E4MX, true>(j, local, smem);
+      else run_job<SRQ_E4MX, false>(j, local, smem);
       break;
   }
 }

@@ -13,12 +13,12 @@ LIB_PATH = os.path.join(HERE, "libsrq.so")
 
 OK = 0
 F32, BF16 = 0, 1
-NONE, INT8, INT4, E4M3, E5M2 = 0, 1, 2, 3, 4
+NONE, INT8, INT4, E4M3, E5M2, E4M2, E4M1, E4M0 = 0, 1, 2, 3, 4, 5, 6, 7
 SR, RTN = 0, 1
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD = 0, 1, 2, 3
 FLAG_F8_PIPELINE = 1
-KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2"}
-QMAX = {INT8: 127.0, INT4: 7.0, E4M3: 448.0, E5M2: 57344.0}
+KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2", E4M2: "e4m2", E4M1: "e4m1", E4M0: "e4m0"}
+QMAX = {INT8: 127.0, INT4: 7.0, E4M3: 448.0, E5M2: 57344.0, E4M2: 448.0, E4M1: 384.0, E4M0: 256.0}
 
 
 class srq_quant(C.Structure):

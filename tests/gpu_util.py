@@ -6,7 +6,7 @@ import oracle
 from paper_2511_00874_amd import lib as L
 
 DEV = "cuda:0"
-KINDS = [L.INT8, L.INT4, L.E4M3, L.E5M2]
+KINDS = [L.INT8, L.INT4, L.E4M3, L.E5M2, L.E4M2, L.E4M1, L.E4M0]
 
 
 def say(*a):

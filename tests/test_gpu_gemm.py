@@ -12,7 +12,7 @@ from gpu_util import (DEV, check_product, check_product_f8_pipeline, group_max_s
 pytestmark = pytest.mark.gpu
 
 PAIRS = [(L.INT8, L.INT8), (L.INT4, L.INT8), (L.E4M3, L.E4M3), (L.E4M3, L.E5M2), (L.E5M2, L.E4M3),
-         (L.E5M2, L.E5M2)]
+         (L.E5M2, L.E5M2), (L.E4M2, L.E5M2), (L.E4M0, L.E4M1)]
 
 
 def _rand_codes(shape, kind, seed):
@@ -22,6 +22,7 @@ def _rand_codes(shape, kind, seed):
     if kind == L.INT4:
         return rng.integers(-7, 8, size=shape).astype(np.int8).view(np.uint8)
     c = rng.integers(0, 256, size=shape).astype(np.uint8)
+    c &= {L.E4M2: 0xFE, L.E4M1: 0xFC, L.E4M0: 0xF8}.get(kind, 0xFF)   # sub-grids of E4M3: low fraction bits zero
     bad = ~np.isfinite(oracle.decode_array(kind, c))   # NaN / Inf codes never come out of the quantizer
     c[bad] = 0x30
     return c
@@ -185,6 +186,7 @@ def test_single_layer_int8_all_five_quantizers():
     {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.E5M2, "W_bwd": L.E5M2, "dY_bwd": L.E5M2},
     {"A_fwd": L.E4M3, "W_fwd": L.E4M3, "A_bwd": L.E4M3, "W_bwd": L.E4M3, "dY_bwd": L.E5M2},
     {"A_fwd": L.INT8, "W_fwd": L.INT4, "A_bwd": L.INT8, "W_bwd": L.INT8, "dY_bwd": L.INT4},
+    {"A_fwd": L.E4M2, "W_fwd": L.E4M2, "A_bwd": L.E4M1, "W_bwd": L.E4M1, "dY_bwd": L.E4M0},
 ])
 def test_ragged_layer_mixed_formats(kinds):
     t = _layer(272, 144, 208, 3, std_dy=1e-3, w_bf16=True)

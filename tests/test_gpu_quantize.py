@@ -140,7 +140,7 @@ def test_statistics_on_gpu_match_the_paper_example():
     assert np.all(rtn == 1)
 
 
-@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("kind", [L.INT8, L.INT4, L.E4M3, L.E5M2, L.E4M1])
 def test_full_size_standalone_quantize_bit_exact(kind):
     # the 2^28-element workload of the standalone quantizer, in the launch shape bench.py times
     n = 1 << 28
