@@ -67,17 +67,26 @@ class Layer:
         self.Y = torch.empty((M, N), dtype=torch.float32, device=dev)
         self.dA = torch.empty((M, K), dtype=torch.float32, device=dev)
         self.dW = torch.empty((N, K), dtype=torch.float32, device=dev)
-        need = max(L.sr_linear_workspace_bytes(op, M, N, K) for op in (L.OP_FWD, L.OP_BWD))
+        need = max(L.sr_linear_workspace_bytes(op, M, N, K) for op in (L.OP_FWD, L.OP_BWD, L.OP_FWD_STASH, L.OP_BWD_STASHED))
         self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        self.stash = torch.empty(L.sr_linear_stash_bytes(M, N, K), dtype=torch.uint8, device=dev)
         self.absmax = L.AbsmaxBatch([(t, kind, s) for t, kind, s in self.src_of.values()])
 
     def step(self, L):
-        # a0: five scales (three passes: A and W feed two formats each); a1-a5: forward, then the
-        # backward pass with one Q(dY) for both products
+        # a0: five scales (three passes: A and W feed two formats each); a1-a5: the forward pass,
+        # whose one read of A and W also yields their backward codes (all five quantizers run, each
+        # tensor is read once per step), then the backward pass with one Q(dY) for both products
         self.absmax.run()
-        L.sr_linear_fwd(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], out=self.Y, workspace=self.ws)
-        L.sr_linear_bwd(self.dY, self.W, self.A, self.q["dY_bwd"], self.q["W_bwd"], self.q["A_bwd"],
-                        out_dA=self.dA, out_dW=self.dW, workspace=self.ws)
+        self.forward(L)
+        self.backward(L)
+
+    def forward(self, L):
+        L.sr_linear_fwd_stash(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], self.q["A_bwd"], self.q["W_bwd"],
+                              stash=self.stash, out=self.Y, workspace=self.ws)
+
+    def backward(self, L):
+        L.sr_linear_bwd_stashed(self.dY, self.stash, self.K, self.q["dY_bwd"], self.q["W_bwd"], self.q["A_bwd"],
+                                out_dA=self.dA, out_dW=self.dW, workspace=self.ws)
 
     def flops(self):
         return 6.0 * self.M * self.N * self.K
@@ -219,12 +228,11 @@ def phase_times(L, torch, layers, reps):
 
     def fwd():
         for ly in layers:
-            L.sr_linear_fwd(ly.A, ly.W, ly.q["A_fwd"], ly.q["W_fwd"], out=ly.Y, workspace=ly.ws)
+            ly.forward(L)
 
     def bwd():
         for ly in layers:
-            L.sr_linear_bwd(ly.dY, ly.W, ly.A, ly.q["dY_bwd"], ly.q["W_bwd"], ly.q["A_bwd"],
-                            out_dA=ly.dA, out_dW=ly.dW, workspace=ly.ws)
+            ly.backward(L)
     res = {n: round(event_ms(torch, f, reps) * 1e3, 1) for n, f in (("absmax_us", absmax), ("fwd_us", fwd), ("bwd_us", bwd))}
     nbytes = sum(4 * (ly.A.numel() + ly.W.numel() + ly.dY.numel()) for ly in layers)
     res["absmax_GB/s"] = round(nbytes / (res["absmax_us"] * 1e-6) / 1e9, 1)

@@ -103,7 +103,8 @@ typedef struct {
  * rounding).  Integer formats ignore the flag: their products are exact in int32. */
 enum { SRQ_FLAG_F8_PIPELINE = 1 };
 
-enum { SRQ_OP_FWD = 0, SRQ_OP_BWD_DATA = 1, SRQ_OP_BWD_WEIGHT = 2, SRQ_OP_BWD = 3 };
+enum { SRQ_OP_FWD = 0, SRQ_OP_BWD_DATA = 1, SRQ_OP_BWD_WEIGHT = 2, SRQ_OP_BWD = 3, SRQ_OP_FWD_STASH = 4,
+       SRQ_OP_BWD_STASHED = 5 };
 
 /* Per-tensor scale for absmax scaling (a choice of Delta; the paper leaves Delta open):
  * *scale_out_dev = max|x_i| / Qmax(kind) over the finite elements, or 1 if that is zero.
@@ -185,6 +186,31 @@ int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void*
                   const void* A, int dtypeA, size_t M, size_t N, size_t K, const srq_quant* qdY_bwd,
                   const srq_quant* qW_bwd, const srq_quant* qA_bwd, float beta, void* workspace,
                   size_t workspace_bytes, void* stream);
+
+/* Alg. 1 and Alg. 2 with the backward operands of A and W saved in code form by the forward
+ * pass ("saved for backward" as codes): A and W are read once per step instead of twice, and the
+ * caller need not keep A in binary32 for the backward pass.
+ *
+ * sr_linear_fwd_stash computes Y exactly as sr_linear_fwd(.., qA_fwd, qW_fwd) does and, in the
+ * same pass over A and W, writes Q(A; qA_bwd)^T and Q(W; qW_bwd)^T -- the very codes
+ * sr_linear_bwd would produce -- into `stash` (device, 256-byte aligned, at least
+ * sr_linear_stash_bytes(M, N, K) bytes, owned by the caller, opaque).  qA_fwd and qW_fwd must be
+ * integer formats (else SRQ_ERR_UNSUPPORTED); qA_bwd and qW_bwd any pair a product accepts.
+ * sr_linear_bwd_stashed then gives dA and dW bit for bit as sr_linear_bwd would with the same
+ * three backward quantizers, reading only dY; qA_bwd and qW_bwd must be the ones the stash was
+ * written with (their scales multiply the results; their formats select the product pipeline).
+ * workspace: sr_linear_workspace_bytes(SRQ_OP_FWD_STASH / SRQ_OP_BWD_STASHED, M, N, K).
+ * Errors as for sr_linear_fwd / sr_linear_bwd; a stash that is NULL, misaligned or too small is
+ * SRQ_ERR_WORKSPACE. */
+size_t sr_linear_stash_bytes(size_t M, size_t N, size_t K);
+int sr_linear_fwd_stash(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
+                        size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd, const srq_quant* qA_bwd,
+                        const srq_quant* qW_bwd, void* stash, size_t stash_bytes, void* workspace,
+                        size_t workspace_bytes, void* stream);
+int sr_linear_bwd_stashed(float* dA, float* dW, const void* dY, int dtypedY, size_t M, size_t N, size_t K,
+                          const srq_quant* qdY_bwd, const srq_quant* qW_bwd, const srq_quant* qA_bwd,
+                          const void* stash, size_t stash_bytes, float beta, void* workspace,
+                          size_t workspace_bytes, void* stream);
 
 /* Weight update of Eq. 10 with the weights stored in bfloat16, in place:
  *     w[i] <- Q(w[i] - eta * g[i]),   i in [0, n)

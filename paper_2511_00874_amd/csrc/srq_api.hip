@@ -65,7 +65,18 @@ QuantJob make_job(const srq_quant* q, const void* x, int dtype, size_t rows, siz
   j.kind = q->kind; j.round = q->round; j.dtype = dtype; j.store = store; j.transpose = transpose;
   j.scale = q->scale; j.scale_dev = q->scale_dev;
   j.seed = q->seed; j.counter_offset = q->counter_offset;
+  j.kind2 = 0; j.round2 = SRQ_SR; j.scale2 = 1.0f; j.scale_dev2 = nullptr; j.seed2 = j.counter_offset2 = 0;
   j.first_block = j.nblocks = 0;
+  return j;
+}
+
+// A transposing job that also writes, in the source layout, the byte codes of a second
+// (integer) quantizer of the same tensor.
+QuantJob make_dual_job(const srq_quant* q, const srq_quant* q2, const void* x, int dtype, size_t rows, size_t cols,
+                       int store, uint8_t* out_t, uint8_t* out2) {
+  QuantJob j = make_job(q, x, dtype, rows, cols, 1, store, out_t, out2);
+  j.kind2 = q2->kind; j.round2 = q2->round; j.scale2 = q2->scale; j.scale_dev2 = q2->scale_dev;
+  j.seed2 = q2->seed; j.counter_offset2 = q2->counter_offset;
   return j;
 }
 
@@ -302,6 +313,12 @@ size_t sr_linear_workspace_bytes(int op, size_t M, size_t N, size_t K) {
     case SRQ_OP_BWD_WEIGHT: return product_bytes_max(N, K, M);  // dW (N x K), contraction M
     case SRQ_OP_BWD:                                            // both; dY is held in both layouts
       return product_bytes_max(M, K, N) + product_bytes_max(N, K, M);
+    case SRQ_OP_FWD_STASH: return product_bytes_max(M, N, K);
+    case SRQ_OP_BWD_STASHED:                                    // dY in both layouts + the two products' scratch
+      return 2 * align_up(2 * M * N, WS_ALIGN) + align_up(gemm_workspace_bytes(M, K, N, PIPE_BF16), WS_ALIGN) +
+             align_up(gemm_workspace_bytes(N, K, M, PIPE_BF16), WS_ALIGN) +
+             align_up(gemm_workspace_bytes(M, K, N, PIPE_I8), WS_ALIGN) +
+             align_up(gemm_workspace_bytes(N, K, M, PIPE_I8), WS_ALIGN);
     default: return 0;
   }
 }
@@ -385,6 +402,93 @@ int sr_update_bf16(void* w_bf16, const float* g, float eta, size_t n, int round_
                             static_cast<hipStream_t>(stream)) == hipSuccess
              ? SRQ_OK
              : SRQ_ERR_HIP;
+}
+
+size_t sr_linear_stash_bytes(size_t M, size_t N, size_t K) {
+  return align_up(2 * K * M, WS_ALIGN) + align_up(2 * K * N, WS_ALIGN);
+}
+
+// Alg. 1 that also leaves behind what Alg. 2 needs of A and W: one pass over A and one over W
+// feed the forward quantizers (row-major byte codes, into the workspace) and the backward
+// quantizers (transposed, in the form the backward products read, into the stash).
+int sr_linear_fwd_stash(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
+                        size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd, const srq_quant* qA_bwd,
+                        const srq_quant* qW_bwd, void* stash, size_t stash_bytes, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  if (!Y) return SRQ_ERR_NULL;
+  int st = check_operand(A, dtypeA, qA_fwd);
+  if (st != SRQ_OK) return st;
+  st = check_operand(W, dtypeW, qW_fwd);
+  if (st != SRQ_OK) return st;
+  if ((st = check_quant(qA_bwd)) != SRQ_OK || (st = check_quant(qW_bwd)) != SRQ_OK) return st;
+  st = check_dims(M, N, K);
+  if (st != SRQ_OK) return st;
+  if (!aligned16(Y)) return SRQ_ERR_ALIGN;
+  // the rider quantizer is the integer one
+  if (!kind_is_int(qA_fwd->kind) || !kind_is_int(qW_fwd->kind)) return SRQ_ERR_UNSUPPORTED;
+  ProductPlan pf;
+  st = plan_product(pf, qA_fwd, qW_fwd, M, N, K);
+  if (st != SRQ_OK) return st;
+  // the stored form of the backward operands: the pipeline their products with dY will use
+  if (check_pair(qA_bwd->kind, qW_bwd->kind) != SRQ_OK) return SRQ_ERR_UNSUPPORTED;
+  const int stash_pipe = pick_pipe(qA_bwd, qW_bwd);
+  if (stash_pipe < 0) return SRQ_ERR_UNSUPPORTED;
+  if (!workspace_ok(workspace, workspace_bytes, pf.x_bytes + pf.z_bytes + pf.gemm_bytes)) return SRQ_ERR_WORKSPACE;
+  if (!workspace_ok(stash, stash_bytes, sr_linear_stash_bytes(M, N, K))) return SRQ_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint8_t* a_codes = static_cast<uint8_t*>(workspace);
+  uint8_t* w_codes = a_codes + pf.x_bytes;
+  void* gws = w_codes + pf.z_bytes;
+  uint8_t* a_t = static_cast<uint8_t*>(stash);
+  uint8_t* w_t = a_t + align_up(2 * K * M, WS_ALIGN);
+  const int store = stash_pipe == PIPE_BF16 ? STORE_BF16 : STORE_BYTE;
+  QuantJobs jobs;
+  jobs.njobs = 2;
+  jobs.job[0] = make_dual_job(qA_bwd, qA_fwd, A, dtypeA, M, K, store, a_t, a_codes);
+  jobs.job[1] = make_dual_job(qW_bwd, qW_fwd, W, dtypeW, N, K, store, w_t, w_codes);
+  if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  return launch_product(Y, a_codes, qA_fwd, w_codes, qW_fwd, M, N, K, pf, 0.0f, gws, s);
+}
+
+// Alg. 2 from the stash of sr_linear_fwd_stash: only dY is read and quantized here.
+int sr_linear_bwd_stashed(float* dA, float* dW, const void* dY, int dtypedY, size_t M, size_t N, size_t K,
+                          const srq_quant* qdY_bwd, const srq_quant* qW_bwd, const srq_quant* qA_bwd,
+                          const void* stash, size_t stash_bytes, float beta, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!dA || !dW) return SRQ_ERR_NULL;
+  int st = check_operand(dY, dtypedY, qdY_bwd);
+  if (st != SRQ_OK) return st;
+  if ((st = check_quant(qA_bwd)) != SRQ_OK || (st = check_quant(qW_bwd)) != SRQ_OK) return st;
+  st = check_dims(M, N, K);
+  if (st != SRQ_OK) return st;
+  if (!aligned16(dA) || !aligned16(dW)) return SRQ_ERR_ALIGN;
+  if (beta != 0.0f && beta != 1.0f) return SRQ_ERR_UNSUPPORTED;
+  ProductPlan pd, pw;
+  st = plan_product(pd, qdY_bwd, qW_bwd, M, K, N);
+  if (st != SRQ_OK) return st;
+  st = plan_product(pw, qdY_bwd, qA_bwd, N, K, M);
+  if (st != SRQ_OK) return st;
+  // all three operands in one stored form, the one the stash was written in
+  if (pd.pipe != pw.pipe || check_pair(qA_bwd->kind, qW_bwd->kind) != SRQ_OK || pick_pipe(qA_bwd, qW_bwd) != pd.pipe)
+    return SRQ_ERR_UNSUPPORTED;
+  const size_t need = pd.x_bytes + pd.gemm_bytes + pw.x_bytes + pw.gemm_bytes;
+  if (!workspace_ok(workspace, workspace_bytes, need)) return SRQ_ERR_WORKSPACE;
+  if (!workspace_ok(stash, stash_bytes, sr_linear_stash_bytes(M, N, K))) return SRQ_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint8_t* dy_rm = static_cast<uint8_t*>(workspace);  // M x N
+  uint8_t* gws_d = dy_rm + pd.x_bytes;
+  uint8_t* dy_t = gws_d + pd.gemm_bytes;              // N x M
+  uint8_t* gws_w = dy_t + pw.x_bytes;
+  const uint8_t* a_t = static_cast<const uint8_t*>(stash);
+  const uint8_t* w_t = a_t + align_up(2 * K * M, WS_ALIGN);
+  const int store = pd.pipe == PIPE_BF16 ? STORE_BF16 : STORE_BYTE;
+  QuantJobs jobs;
+  jobs.njobs = 1;
+  jobs.job[0] = make_job(qdY_bwd, dY, dtypedY, M, N, 1, store, dy_t, dy_rm);
+  if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  st = launch_product(dA, dy_rm, qdY_bwd, w_t, qW_bwd, M, K, N, pd, 0.0f, gws_d, s);
+  if (st != SRQ_OK) return st;
+  return launch_product(dW, dy_t, qdY_bwd, a_t, qA_bwd, N, K, M, pw, beta, gws_w, s);
 }
 
 const char* sr_status_string(int status) {

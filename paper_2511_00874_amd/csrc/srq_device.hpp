@@ -82,6 +82,10 @@ template <> struct Grid<SRQ_E4MX> {
   static constexpr int mbits = 0, emin = -6;                                  // mbits unused: InvScale::sub_m
 };
 __host__ __device__ constexpr bool kind_is_e4mx(int kind) { return kind >= SRQ_E4M2 && kind <= SRQ_E4M0; }
+// INT8 / INT4 with the clamp as a run-time value (one instantiation serves both): used where a
+// second, integer quantizer rides along with another format's pass over the same tensor.
+constexpr int SRQ_INTX = 101;
+template <> struct Grid<SRQ_INTX> { static constexpr bool is_float = false; static constexpr int qmax = 0; };  // InvScale::sub_qi
 
 // Per-tensor constants of the multiply that produces the grid coordinate.
 struct InvScale {
@@ -89,6 +93,7 @@ struct InvScale {
   float inv16;  // inv * 2^16 (exact): fl32(x * inv16) = fl32(x * inv) * 2^16
   int sub_m;        // SRQ_E4MX only: fraction bits (2, 1, 0)
   float sub_qmax;   // SRQ_E4MX only: 448, 384, 256
+  int sub_qi;       // SRQ_INTX only: Qmax * 2^16 (127 or 7)
 };
 
 // One element through Eq. 1 on grid KIND.  Returns the code in the low 8 bits (integers:
@@ -104,7 +109,7 @@ __device__ __forceinline__ uint32_t quantize_elem(float x, const InvScale& s, ui
   uint32_t code;
   if constexpr (!G::is_float) {
     static_assert(!AS_BF16, "integer grids are stored as bytes");
-    constexpr int QI = G::qmax << 16;
+    const int QI = KIND == SRQ_INTX ? s.sub_qi : (G::qmax << 16);
     const float y16 = __fmul_rn(x, s.inv16);                            // t * 2^16, D = 1
     int u = ROUND == SRQ_SR ? cvt_rpi(y16) : cvt_flr(y16);              // saturating
     u = min(max(u, -QI), QI);                                           // clamp t to +-Qmax
@@ -179,6 +184,7 @@ __device__ __forceinline__ InvScale inv_scale(float scale, const float* scale_de
   s.inv16 = __fmul_rn(s.inv, 65536.0f);
   s.sub_m = SRQ_E4M0 - kind;  // E4M2 -> 2, E4M1 -> 1, E4M0 -> 0
   s.sub_qmax = kind == SRQ_E4M2 ? 448.0f : kind == SRQ_E4M1 ? 384.0f : 256.0f;
+  s.sub_qi = (kind == SRQ_INT4 ? 7 : 127) << 16;
   return s;
 }
 

@@ -32,12 +32,19 @@ constexpr int QUANT_JOBS_MAX = 3;
 struct QuantJob {
   const void* x;
   uint8_t* out;    // rows x cols codes, or cols x rows when transpose
-  uint8_t* out2;   // transpose only: optional extra rows x cols copy (same codes), else nullptr
+  uint8_t* out2;   // transpose only: optional extra rows x cols output, else nullptr:
+                   //   kind2 == 0: the same codes again, in the source layout
+                   //   kind2 == SRQ_INT8 / SRQ_INT4: the byte codes of a second, integer quantizer of the
+                   //   same tensor (its own scale, rounding mode and stream position), source layout
   uint32_t rows, cols;
   int kind, round, dtype, store, transpose;
   float scale;
   const float* scale_dev;
   uint64_t seed, counter_offset;
+  int kind2, round2;
+  float scale2;
+  const float* scale_dev2;
+  uint64_t seed2, counter_offset2;
   uint32_t first_block, nblocks;  // filled by the launcher
 };
 struct QuantJobs {

@@ -70,7 +70,8 @@ __device__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
   }
 }
 
-// transposed output (cols x rows), optionally a same-layout copy as well (out2)
+// transposed output (cols x rows), optionally a same-layout output as well (out2): the same
+// codes, or those of a second (integer) quantizer of the same values
 template <int KIND, bool AS_BF16>
 __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem) {
   using elem_t = typename std::conditional<AS_BF16, uint16_t, uint8_t>::type;
@@ -78,6 +79,7 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
   constexpr int PITCH = TR + 4 / ES;
   elem_t* tile = reinterpret_cast<elem_t*>(smem);
   const InvScale inv = inv_scale(j.scale, j.scale_dev, j.kind);
+  const InvScale inv2 = j.out2 && j.kind2 ? inv_scale(j.scale2, j.scale_dev2, j.kind2) : inv;
   const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
   const uint32_t tiles_x = (j.cols + TC - 1) / TC;
   const uint32_t r0 = (local / tiles_x) * TR, c0 = (local % tiles_x) * TC;
@@ -123,7 +125,7 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
         quantize_quad<KIND, SRQ_RTN, AS_BF16>(ca, a.x, a.y, a.z, a.w, inv, addA);
         quantize_quad<KIND, SRQ_RTN, AS_BF16>(cb, b.x, b.y, b.z, b.w, inv, addB);
       }
-      if (j.out2) {
+      if (j.out2 && j.kind2 == 0) {
         if constexpr (AS_BF16) {
           uint16_t* o = reinterpret_cast<uint16_t*>(j.out2);
           if (okA) *reinterpret_cast<u32x2*>(o + eA) = u32x2{ca[0] | (ca[1] << 16), ca[2] | (ca[3] << 16)};
@@ -132,6 +134,28 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
           if (okA) *reinterpret_cast<uint32_t*>(j.out2 + eA) = pack4_bytes(ca);
           if (okB) *reinterpret_cast<uint32_t*>(j.out2 + eB) = pack4_bytes(cb);
         }
+      } else if (j.out2) {
+        // the second quantizer: its own thresholds (same pairing of lanes and Philox blocks)
+        uint32_t add2A[4], add2B[4], da[4], db[4];
+        if (j.round2 == SRQ_SR) {
+          uint32_t w[4];
+          philox_block(j.counter_offset2 + (odd ? eB : eA) / 8, (uint32_t)j.seed2, (uint32_t)(j.seed2 >> 32), w);
+          const uint32_t nb0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[0], 0xB1, 0xF, 0xF, true);
+          const uint32_t nb1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[1], 0xB1, 0xF, 0xF, true);
+          const uint32_t nb2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[2], 0xB1, 0xF, 0xF, true);
+          const uint32_t nb3 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[3], 0xB1, 0xF, 0xF, true);
+          sr_addends(odd ? nb2 : w[0], odd ? nb3 : w[1], add2A);
+          sr_addends(odd ? w[2] : nb0, odd ? w[3] : nb1, add2B);
+          quantize_quad<SRQ_INTX, SRQ_SR, false>(da, a.x, a.y, a.z, a.w, inv2, add2A);
+          quantize_quad<SRQ_INTX, SRQ_SR, false>(db, b.x, b.y, b.z, b.w, inv2, add2B);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) add2A[e] = add2B[e] = RTN_ADDEND;
+          quantize_quad<SRQ_INTX, SRQ_RTN, false>(da, a.x, a.y, a.z, a.w, inv2, add2A);
+          quantize_quad<SRQ_INTX, SRQ_RTN, false>(db, b.x, b.y, b.z, b.w, inv2, add2B);
+        }
+        if (okA) *reinterpret_cast<uint32_t*>(j.out2 + eA) = pack4_bytes(da);
+        if (okB) *reinterpret_cast<uint32_t*>(j.out2 + eB) = pack4_bytes(db);
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -151,7 +175,17 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
         float v[8];
         job_load_group(v, j, g, n);
         job_quantize_group<KIND, AS_BF16>(c, v, inv, j, g, k0, k1);
-        if (j.out2) store_group<AS_BF16>(j.out2, g * 8, c);
+        if (j.out2 && j.kind2 == 0) {
+          store_group<AS_BF16>(j.out2, g * 8, c);
+        } else if (j.out2) {
+          uint32_t c2[8];
+          if (j.round2 == SRQ_SR)
+            quantize_group<SRQ_INTX, SRQ_SR, false>(c2, v, inv2, j.counter_offset2 + g, (uint32_t)j.seed2,
+                                                    (uint32_t)(j.seed2 >> 32));
+          else
+            quantize_group<SRQ_INTX, SRQ_RTN, false>(c2, v, inv2, 0, 0, 0);
+          store_group<false>(j.out2, g * 8, c2);
+        }
       }
 #pragma unroll
       for (int e = 0; e < 8; ++e) tile[(gc * 8 + e) * PITCH + r] = (elem_t)c[e];

@@ -15,7 +15,7 @@ OK = 0
 F32, BF16 = 0, 1
 NONE, INT8, INT4, E4M3, E5M2, E4M2, E4M1, E4M0 = 0, 1, 2, 3, 4, 5, 6, 7
 SR, RTN = 0, 1
-OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD = 0, 1, 2, 3
+OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD, OP_FWD_STASH, OP_BWD_STASHED = 0, 1, 2, 3, 4, 5
 FLAG_F8_PIPELINE = 1
 KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2", E4M2: "e4m2", E4M1: "e4m1", E4M0: "e4m0"}
 QMAX = {INT8: 127.0, INT4: 7.0, E4M3: 448.0, E5M2: 57344.0, E4M2: 448.0, E4M1: 384.0, E4M0: 256.0}
@@ -59,16 +59,21 @@ _lib.sr_linear_bwd.argtypes = [_vp, _vp, _vp, C.c_int, _vp, C.c_int, _vp, C.c_in
                                C.c_float, _vp, _sz, _vp]
 _lib.sr_linear_workspace_bytes.argtypes = [C.c_int, _sz, _sz, _sz]
 _lib.sr_linear_workspace_bytes.restype = _sz
+_lib.sr_linear_stash_bytes.argtypes = [_sz, _sz, _sz]
+_lib.sr_linear_stash_bytes.restype = _sz
+_lib.sr_linear_fwd_stash.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp, _qp, _vp, _sz, _vp, _sz, _vp]
+_lib.sr_linear_bwd_stashed.argtypes = [_vp, _vp, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp, _vp, _sz, C.c_float, _vp, _sz, _vp]
 _lib.sr_update_bf16.argtypes = [_vp, _vp, C.c_float, _sz, C.c_int, C.c_uint64, C.c_uint64, _vp]
 _lib.sr_status_string.argtypes = [C.c_int]
 _lib.sr_status_string.restype = C.c_char_p
 for _n in ("sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_linear_fwd", "sr_linear_bwd_data",
-           "sr_linear_bwd_weight", "sr_linear_bwd", "sr_update_bf16"):
+           "sr_linear_bwd_weight", "sr_linear_bwd", "sr_update_bf16", "sr_linear_fwd_stash", "sr_linear_bwd_stashed"):
     getattr(_lib, _n).restype = C.c_int
 
 EXPORTS = ["sr_absmax_scale", "sr_absmax_scales", "sr_absmax_workspace_bytes", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes", "sr_gemm_bf16", "sr_gemm_bf16_workspace_bytes",
            "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight", "sr_linear_bwd",
-           "sr_linear_workspace_bytes", "sr_update_bf16", "sr_status_string"]
+           "sr_linear_workspace_bytes", "sr_linear_stash_bytes", "sr_linear_fwd_stash", "sr_linear_bwd_stashed",
+           "sr_update_bf16", "sr_status_string"]
 
 raw = _lib  # the C entry points themselves, for tests of the error paths
 
@@ -155,6 +160,39 @@ class AbsmaxBatch:
 def sr_absmax_scales(requests):
     """requests: [(tensor, kind, out 1-element device tensor)]; all scales in two launches."""
     AbsmaxBatch(requests).run()
+
+
+def sr_linear_stash_bytes(M, N, K):
+    return _lib.sr_linear_stash_bytes(M, N, K)
+
+
+def sr_linear_fwd_stash(A, W, qA, qW, qA_bwd, qW_bwd, stash=None, out=None, workspace=None):
+    """Alg. 1 that also saves Q(A; qA_bwd)^T and Q(W; qW_bwd)^T in code form: returns (Y, stash)."""
+    M, K = A.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    if stash is None:
+        stash = torch.empty(sr_linear_stash_bytes(M, N, K), dtype=torch.uint8, device=A.device)
+    ws = _ws(OP_FWD_STASH, M, N, K, workspace, A.device)
+    _check(_lib.sr_linear_fwd_stash(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K, C.byref(qA.c()),
+                                    C.byref(qW.c()), C.byref(qA_bwd.c()), C.byref(qW_bwd.c()), _dev(stash),
+                                    stash.numel(), _dev(ws), ws.numel(), _stream()))
+    return out, stash
+
+
+def sr_linear_bwd_stashed(dY, stash, K, qdY, qW, qA, out_dA=None, out_dW=None, beta=0.0, workspace=None):
+    """Alg. 2 from the stash of sr_linear_fwd_stash: (dA, dW); only dY is read."""
+    M, N = dY.shape
+    if out_dA is None:
+        out_dA = torch.empty((M, K), dtype=torch.float32, device=dY.device)
+    if out_dW is None:
+        out_dW = torch.empty((N, K), dtype=torch.float32, device=dY.device)
+    ws = _ws(OP_BWD_STASHED, M, N, K, workspace, dY.device)
+    _check(_lib.sr_linear_bwd_stashed(_dev(out_dA), _dev(out_dW), _dev(dY), _dtype(dY), M, N, K, C.byref(qdY.c()),
+                                      C.byref(qW.c()), C.byref(qA.c()), _dev(stash), stash.numel(), beta, _dev(ws),
+                                      ws.numel(), _stream()))
+    return out_dA, out_dW
 
 
 def sr_update_bf16(w, g, eta, seed=0, counter_offset=0, round_mode=SR):

@@ -166,6 +166,18 @@ def _run_layer(t, q, sample=None, beta_check=False, f8_pipeline=False):
         acc = dW2.clone()
         L.sr_linear_bwd(t["dY"], t["W"], t["A"], q["dY_bwd"][0], q["W_bwd"][0], q["A_bwd"][0], out_dW=acc, beta=1.0)
         assert torch.equal(acc, dW2 + dW2)
+    # the pass that saves the backward operands of A and W as codes during the forward pass gives
+    # the very same Y, dA and dW (integer forward formats only)
+    if q["A_fwd"][0].kind in (L.INT8, L.INT4) and q["W_fwd"][0].kind in (L.INT8, L.INT4):
+        Y1 = L.sr_linear_fwd(t["A"], t["W"], q["A_fwd"][0], q["W_fwd"][0])
+        Y3, stash = L.sr_linear_fwd_stash(t["A"], t["W"], q["A_fwd"][0], q["W_fwd"][0], q["A_bwd"][0], q["W_bwd"][0])
+        dA3, dW3 = L.sr_linear_bwd_stashed(t["dY"], stash, K, q["dY_bwd"][0], q["W_bwd"][0], q["A_bwd"][0])
+        assert torch.equal(Y1, Y3), "forward with stash differs"
+        assert torch.equal(dA2, dA3) and torch.equal(dW2, dW3), "backward from the stash differs"
+        if beta_check:
+            acc = dW3.clone()
+            L.sr_linear_bwd_stashed(t["dY"], stash, K, q["dY_bwd"][0], q["W_bwd"][0], q["A_bwd"][0], out_dW=acc, beta=1.0)
+            assert torch.equal(acc, dW3 + dW3)
     if beta_check:
         base = L.sr_linear_bwd_weight(t["dY"], t["A"], q["dY_bwd"][0], q["A_bwd"][0])
         acc = base.clone()
@@ -187,6 +199,7 @@ def test_single_layer_int8_all_five_quantizers():
     {"A_fwd": L.E4M3, "W_fwd": L.E4M3, "A_bwd": L.E4M3, "W_bwd": L.E4M3, "dY_bwd": L.E5M2},
     {"A_fwd": L.INT8, "W_fwd": L.INT4, "A_bwd": L.INT8, "W_bwd": L.INT8, "dY_bwd": L.INT4},
     {"A_fwd": L.E4M2, "W_fwd": L.E4M2, "A_bwd": L.E4M1, "W_bwd": L.E4M1, "dY_bwd": L.E4M0},
+    {"A_fwd": L.INT4, "W_fwd": L.INT8, "A_bwd": L.E4M3, "W_bwd": L.E4M2, "dY_bwd": L.E5M2},
 ])
 def test_ragged_layer_mixed_formats(kinds):
     t = _layer(272, 144, 208, 3, std_dy=1e-3, w_bf16=True)
