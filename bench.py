@@ -67,26 +67,26 @@ class Layer:
         self.Y = torch.empty((M, N), dtype=torch.float32, device=dev)
         self.dA = torch.empty((M, K), dtype=torch.float32, device=dev)
         self.dW = torch.empty((N, K), dtype=torch.float32, device=dev)
-        need = max(L.sr_linear_workspace_bytes(op, M, N, K) for op in (L.OP_FWD, L.OP_BWD, L.OP_FWD_STASH, L.OP_BWD_STASHED))
+        need = max(L.sr_linear_workspace_bytes(op, M, N, K) for op in (L.OP_FWD, L.OP_BWD))
         self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
-        self.stash = torch.empty(L.sr_linear_stash_bytes(M, N, K), dtype=torch.uint8, device=dev)
         self.absmax = L.AbsmaxBatch([(t, kind, s) for t, kind, s in self.src_of.values()])
 
     def step(self, L):
-        # a0: five scales (three passes: A and W feed two formats each); a1-a5: the forward pass,
-        # whose one read of A and W also yields their backward codes (all five quantizers run, each
-        # tensor is read once per step), then the backward pass with one Q(dY) for both products
+        # a0: five scales (three passes: A and W feed two formats each); a1-a5: forward, then the
+        # backward pass with one Q(dY) for both products.  (The variant that saves the backward
+        # codes of A and W during the forward pass, sr_linear_fwd_stash, moves fewer bytes but is
+        # no faster here: its forward quantizer does two quantizations per element loaded and its
+        # products read operands that have left the last-level cache.  It is there to save memory.)
         self.absmax.run()
         self.forward(L)
         self.backward(L)
 
     def forward(self, L):
-        L.sr_linear_fwd_stash(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], self.q["A_bwd"], self.q["W_bwd"],
-                              stash=self.stash, out=self.Y, workspace=self.ws)
+        L.sr_linear_fwd(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], out=self.Y, workspace=self.ws)
 
     def backward(self, L):
-        L.sr_linear_bwd_stashed(self.dY, self.stash, self.K, self.q["dY_bwd"], self.q["W_bwd"], self.q["A_bwd"],
-                                out_dA=self.dA, out_dW=self.dW, workspace=self.ws)
+        L.sr_linear_bwd(self.dY, self.W, self.A, self.q["dY_bwd"], self.q["W_bwd"], self.q["A_bwd"],
+                        out_dA=self.dA, out_dW=self.dW, workspace=self.ws)
 
     def flops(self):
         return 6.0 * self.M * self.N * self.K

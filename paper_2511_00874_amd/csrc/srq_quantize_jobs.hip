@@ -4,6 +4,7 @@
 // read once.  A workgroup first finds its job, then runs the same-layout or the transposing
 // path for that job's format; format, source dtype and rounding mode are uniform per
 // workgroup, so the dispatch is scalar branches.
+#include <cstddef>
 #include <type_traits>
 
 #include "srq_device.hpp"
@@ -218,7 +219,18 @@ __global__ __launch_bounds__(QBLOCK) void quantize_jobs_kernel(QuantJobs jobs) {
 #pragma unroll
   for (int i = 1; i < QUANT_JOBS_MAX; ++i)
     if (i < jobs.njobs && blockIdx.x >= jobs.job[i].first_block) ji = i;
-  const QuantJob& j = jobs.job[ji];
+  // The job descriptor is workgroup-uniform.  Indexing the by-value argument with ji would make
+  // the compiler copy the whole argument to per-lane scratch memory; instead the one descriptor
+  // is read from the kernel-argument segment (constant address space, scalar loads), where the
+  // explicit arguments start at offset 0.
+  struct alignas(8) Raw { uint32_t w[sizeof(QuantJob) / 4]; } raw;
+  static_assert(sizeof(QuantJob) % 4 == 0 && offsetof(QuantJobs, job) % 4 == 0, "descriptor is read word-wise");
+  typedef __attribute__((address_space(4))) const uint32_t* kernarg_words;
+  const kernarg_words kw = (kernarg_words)__builtin_amdgcn_kernarg_segment_ptr() +
+                           (offsetof(QuantJobs, job) + (size_t)ji * sizeof(QuantJob)) / 4;
+#pragma unroll
+  for (unsigned k = 0; k < sizeof(QuantJob) / 4; ++k) raw.w[k] = kw[k];
+  const QuantJob j = __builtin_bit_cast(QuantJob, raw);
   const uint32_t local = blockIdx.x - j.first_block;
   const bool bf = j.store == STORE_BF16;
   switch (j.kind) {
