@@ -51,7 +51,10 @@ int pick_pipe(const srq_quant* qx, const srq_quant* qz) {
   if (kind_is_int(qx->kind)) return PIPE_I8;
   const bool fx = qx->flags & SRQ_FLAG_F8_PIPELINE, fz = qz->flags & SRQ_FLAG_F8_PIPELINE;
   if (fx != fz) return -1;
-  return fx ? PIPE_F8 : PIPE_BF16;
+  if (fx) return PIPE_F8;
+  // exact pipelines: E5M2 x E5M2 multiplies straight from the one-byte codes; anything with an
+  // E4M3-family operand goes through the bfloat16 form
+  return qx->kind == SRQ_E5M2 && qz->kind == SRQ_E5M2 ? PIPE_F16C : PIPE_BF16;
 }
 
 // int32 accumulation is exact while R * 127^2 < 2^31
@@ -104,12 +107,16 @@ struct ProductPlan {
   size_t es, x_bytes, z_bytes, gemm_bytes;
 };
 
-int plan_product(ProductPlan& pp, const srq_quant* qx, const srq_quant* qz, size_t P, size_t Q, size_t R) {
+// from_codes = false: an operand shared with another product is stored as bfloat16 there, so
+// this product may not use the pipeline that reads one-byte E5M2 codes.
+int plan_product(ProductPlan& pp, const srq_quant* qx, const srq_quant* qz, size_t P, size_t Q, size_t R,
+                 bool from_codes = true) {
   int st = check_pair(qx->kind, qz->kind);
   if (st != SRQ_OK) return st;
   if (!int_contraction_ok(qx->kind, R)) return SRQ_ERR_UNSUPPORTED;
   pp.pipe = pick_pipe(qx, qz);
   if (pp.pipe < 0) return SRQ_ERR_UNSUPPORTED;
+  if (pp.pipe == PIPE_F16C && !from_codes) pp.pipe = PIPE_BF16;
   if (!gemm_operands_addressable(P, Q, R, pp.pipe)) return SRQ_ERR_UNSUPPORTED;
   pp.es = pp.pipe == PIPE_BF16 ? 2 : 1;
   pp.x_bytes = align_up(P * R * pp.es, WS_ALIGN);
@@ -364,9 +371,11 @@ int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void*
   if (!aligned16(dA) || !aligned16(dW)) return SRQ_ERR_ALIGN;
   if (beta != 0.0f && beta != 1.0f) return SRQ_ERR_UNSUPPORTED;
   ProductPlan pd, pw;  // dA = dY (M x N) . Wt (K x N)^T ;  dW = dYt (N x M) . At (K x M)^T
-  st = plan_product(pd, qdY_bwd, qW_bwd, M, K, N);
+  // Q(dY) is stored once for both products: one-byte codes only if all three formats are E5M2
+  const bool codes = qW_bwd->kind == SRQ_E5M2 && qA_bwd->kind == SRQ_E5M2;
+  st = plan_product(pd, qdY_bwd, qW_bwd, M, K, N, codes);
   if (st != SRQ_OK) return st;
-  st = plan_product(pw, qdY_bwd, qA_bwd, N, K, M);
+  st = plan_product(pw, qdY_bwd, qA_bwd, N, K, M, codes);
   if (st != SRQ_OK) return st;
   if (pd.pipe != pw.pipe) return SRQ_ERR_UNSUPPORTED;  // one stored form of Q(dY) serves both products
   const size_t need = pd.x_bytes + pd.z_bytes + pd.gemm_bytes + pw.x_bytes + pw.z_bytes + pw.gemm_bytes;
@@ -464,13 +473,15 @@ int sr_linear_bwd_stashed(float* dA, float* dW, const void* dY, int dtypedY, siz
   if (!aligned16(dA) || !aligned16(dW)) return SRQ_ERR_ALIGN;
   if (beta != 0.0f && beta != 1.0f) return SRQ_ERR_UNSUPPORTED;
   ProductPlan pd, pw;
-  st = plan_product(pd, qdY_bwd, qW_bwd, M, K, N);
+  // all three operands in one stored form, the one the stash was written in (one-byte codes
+  // when A and W are both E5M2, which then needs an E5M2 dY as well)
+  if (check_pair(qA_bwd->kind, qW_bwd->kind) != SRQ_OK) return SRQ_ERR_UNSUPPORTED;
+  const int stash_pipe = pick_pipe(qA_bwd, qW_bwd);
+  st = plan_product(pd, qdY_bwd, qW_bwd, M, K, N, stash_pipe == PIPE_F16C);
   if (st != SRQ_OK) return st;
-  st = plan_product(pw, qdY_bwd, qA_bwd, N, K, M);
+  st = plan_product(pw, qdY_bwd, qA_bwd, N, K, M, stash_pipe == PIPE_F16C);
   if (st != SRQ_OK) return st;
-  // all three operands in one stored form, the one the stash was written in
-  if (pd.pipe != pw.pipe || check_pair(qA_bwd->kind, qW_bwd->kind) != SRQ_OK || pick_pipe(qA_bwd, qW_bwd) != pd.pipe)
-    return SRQ_ERR_UNSUPPORTED;
+  if (pd.pipe != pw.pipe || pd.pipe != stash_pipe) return SRQ_ERR_UNSUPPORTED;
   const size_t need = pd.x_bytes + pd.gemm_bytes + pw.x_bytes + pw.gemm_bytes;
   if (!workspace_ok(workspace, workspace_bytes, need)) return SRQ_ERR_WORKSPACE;
   if (!workspace_ok(stash, stash_bytes, sr_linear_stash_bytes(M, N, K))) return SRQ_ERR_WORKSPACE;

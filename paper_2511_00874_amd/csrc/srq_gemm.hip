@@ -7,6 +7,9 @@
 // operands with the contraction index contiguous.  Three matrix pipelines:
 //   int8 codes          v_mfma_i32_32x32x32_i8        int32 accumulators, exact
 //   E4M3/E5M2 as bf16   v_mfma_f32_32x32x16_bf16      exact products, binary32 sums
+//   E5M2 codes as f16   v_mfma_f32_32x32x16_f16       the same, from one-byte codes: an E5M2 code is the
+//                                                     high byte of the binary16 number of the same value,
+//                                                     so the operands are widened in registers
 //   E4M3/E5M2 codes     v_mfma_f32_32x32x64_f8f6f4    fp8 pipeline (aligns groups of 8 products)
 //
 // Kernel shape.  A workgroup owns a BM x BN output tile, its waves a WGM x WGN grid of
@@ -31,13 +34,18 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr int BK = 128;  // bytes of contraction per LDS stage
 
+// raw_t: what a lane reads from LDS for one contraction sub-step (a multiple of 16 bytes);
+// frag_t: what the MFMA(s) of that sub-step consume; expand() turns one into the other.
 struct I8Mma {
   using acc_t = v16i;
+  using raw_t = v4i;
   using frag_t = v4i;
+  static __device__ __forceinline__ frag_t expand(raw_t r) { return r; }
   static constexpr int KSTEP = 32;  // contraction bytes per MFMA
   static __device__ __forceinline__ acc_t mma(frag_t a, frag_t b, acc_t c) {
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
@@ -52,7 +60,9 @@ struct I8Mma {
 // eight products of a group to 14 bits before adding them.
 struct BF16Mma {
   using acc_t = v16f;
+  using raw_t = v4i;
   using frag_t = v4i;  // 8 bfloat16
+  static __device__ __forceinline__ frag_t expand(raw_t r) { return r; }
   static constexpr int KSTEP = 32;  // bytes: 16 elements per MFMA
   static __device__ __forceinline__ acc_t mma(frag_t a, frag_t b, acc_t c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c,
@@ -67,10 +77,43 @@ struct BF16Mma {
 template <int FA, int FB>
 struct F8Mma {
   using acc_t = v16f;
+  using raw_t = v8i;
   using frag_t = v8i;
+  static __device__ __forceinline__ frag_t expand(raw_t r) { return r; }
   static constexpr int KSTEP = 64;
   static __device__ __forceinline__ acc_t mma(frag_t a, frag_t b, acc_t c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, FA, FB, 0, 0, 0, 0);
+  }
+  static __device__ __forceinline__ float to_f32(float v) { return v; }
+  static __device__ __forceinline__ float from_bits(uint32_t b) { return __uint_as_float(b); }
+  static __device__ __forceinline__ uint32_t bits(float v) { return __float_as_uint(v); }
+};
+
+// E5M2 codes on the f16 pipeline.  E5M2 is binary16 cut to its high byte, so (code << 8) is the
+// binary16 number of the same value (subnormals included; the MFMA honours binary16 subnormals).
+// A lane reads 16 codes per sub-step and widens them with four byte permutes into two operands
+// of 8 halves: one sub-step is two MFMAs of depth 16.  Products are exact (6-bit significands),
+// sums binary32, as on the bf16 pipeline, with half the operand bytes through LDS.
+struct E5M2F16Mma {
+  using acc_t = v16f;
+  using raw_t = v4i;   // 16 codes
+  using frag_t = v8i;  // 16 halves: codes 0..7, then 8..15
+  static constexpr int KSTEP = 32;  // 32 codes (two lane groups of 16) per sub-step
+  static __device__ __forceinline__ frag_t expand(raw_t r) {
+    frag_t f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t d = (uint32_t)r[c];
+      f[(c >> 1) * 4 + (c & 1) * 2 + 0] = (int)__builtin_amdgcn_perm(d, d, 0x010c000cu);  // codes 0,1 -> high bytes
+      f[(c >> 1) * 4 + (c & 1) * 2 + 1] = (int)__builtin_amdgcn_perm(d, d, 0x030c020cu);  // codes 2,3
+    }
+    return f;
+  }
+  static __device__ __forceinline__ acc_t mma(frag_t a, frag_t b, acc_t c) {
+    const v4i a0 = {a[0], a[1], a[2], a[3]}, a1 = {a[4], a[5], a[6], a[7]};
+    const v4i b0 = {b[0], b[1], b[2], b[3]}, b1 = {b[4], b[5], b[6], b[7]};
+    c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a0), __builtin_bit_cast(v8h, b0), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a1), __builtin_bit_cast(v8h, b1), c, 0, 0, 0);
   }
   static __device__ __forceinline__ float to_f32(float v) { return v; }
   static __device__ __forceinline__ float from_bits(uint32_t b) { return __uint_as_float(b); }
@@ -131,7 +174,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
   static_assert((STAGES - 2) * LPW <= 63 && STAGES >= 2, "vmcnt range");
   using acc_t = typename MMA::acc_t;
   using frag_t = typename MMA::frag_t;
-  constexpr int FC = sizeof(frag_t) / 16;  // 16-byte chunks per lane per MFMA
+  using raw_t = typename MMA::raw_t;
+  constexpr int FC = sizeof(raw_t) / 16;  // 16-byte chunks a lane reads per sub-step
   constexpr int KSUB = BK / MMA::KSTEP;
 
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -207,7 +251,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
     zoff[t] = BM * BK + (wq * WTN + (lane & 31u)) * BK + ((swz ^ tt) << 4);
   }
   auto load_frag = [&](const uint8_t* stage, const uint32_t (&off)[KSUB * FC], int sub, int ks) {
-    frag_t f;
+    raw_t f;
 #pragma unroll
     for (int c = 0; c < FC; ++c) {
       const v4i part = *reinterpret_cast<const v4i*>(stage + off[ks * FC + c] + sub * 32 * BK);
@@ -233,7 +277,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
   constexpr int PF = KSUB > 2 ? 2 : 1;
   auto compute = [&](int buf) {
     const uint8_t* stage = lds + buf * STAGE;
-    frag_t xf[PF + 1][TM], zf[PF + 1][TN];
+    raw_t xf[PF + 1][TM], zf[PF + 1][TN];
     auto fetch = [&](int ks) {
 #pragma unroll
       for (int i = 0; i < TM; ++i) xf[ks % (PF + 1)][i] = load_frag(stage, xoff, i, ks);
@@ -246,11 +290,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
     for (int ks = 0; ks < KSUB; ++ks) {
       if (ks + PF < KSUB) fetch(ks + PF);
       __builtin_amdgcn_sched_barrier(0);
+      // operands are widened (if the pipeline needs it) only now, next to their MFMAs, so the
+      // prefetched reads above stay in flight
+      frag_t xe[TM], ze[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) xe[i] = MMA::expand(xf[ks % (PF + 1)][i]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) ze[j] = MMA::expand(zf[ks % (PF + 1)][j]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = MMA::mma(zf[ks % (PF + 1)][j], xf[ks % (PF + 1)][i], acc[i][j]);  // MFMA rows: q, columns: p
+        for (int j = 0; j < TN; ++j) acc[i][j] = MMA::mma(ze[j], xe[i], acc[i][j]);  // MFMA rows: q, columns: p
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -458,6 +508,7 @@ hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint
   g.accumulate = accumulate ? 1 : 0;
   if (pipe == PIPE_I8) return launch_mma<I8Mma>(g, pl, stream);
   if (pipe == PIPE_BF16) return launch_mma<BF16Mma>(g, pl, stream);
+  if (pipe == PIPE_F16C) return launch_mma<E5M2F16Mma>(g, pl, stream);
   // the Z operand is the first MFMA operand, X the second
   const int fx = kindX == SRQ_E5M2, fz = kindZ == SRQ_E5M2;
   if (!fz && !fx) return launch_mma<F8Mma<0, 0>>(g, pl, stream);

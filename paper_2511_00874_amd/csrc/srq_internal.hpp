@@ -90,7 +90,9 @@ struct GemmScale {
 enum Pipe {
   PIPE_I8 = 0,   // int8 codes, int32 accumulators (exact)
   PIPE_F8 = 1,   // E4M3 / E5M2 codes on the fp8 pipeline (hardware aligns groups of 8 products)
-  PIPE_BF16 = 2  // E4M3 / E5M2 grid values widened to bfloat16: exact products, binary32 sums
+  PIPE_BF16 = 2, // E4M3 / E5M2 grid values widened to bfloat16: exact products, binary32 sums
+  PIPE_F16C = 3  // E5M2 codes (both operands), widened to binary16 inside the kernel: the same arithmetic
+                 // as PIPE_BF16 from one byte per element
 };
 // R is the contraction length in elements; operand rows hold R bytes (PIPE_I8, PIPE_F8) or
 // 2 R bytes (PIPE_BF16).
