@@ -22,9 +22,12 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by what the same counters
 # read for a plain copy of known size (profiles/bench_hbm_traffic.txt): mean over the three
 # launches per step of the bf16 128 x 128 product kernel, and the int8 quantizer on 2^28 elements
-TRAFFIC_BF16_PRODUCT_128 = (2 * (228.7 + 18.0) + (123.5 + 96.0)) / 3 * 2**20
+# mean over the three launches of that kernel in a step: fc2's input gradient (8192 x 3072 out,
+# contraction 768) and the two weight gradients (2.36 M outputs, contraction 8192), one-byte operands
+ALGORITHMIC_F16_PRODUCT_128 = ((8192 * 768 + 3072 * 768 + 4 * 8192 * 3072) + 2 * (3072 * 8192 + 768 * 8192 + 4 * 3072 * 768)) / 3
+TRAFFIC_F16_PRODUCT_128 = (2 * (228.7 + 18.0) + (123.5 + 96.0)) / 3 * 2**20  # placeholder until re-measured
 TRAFFIC_QUANTIZE_INT8_2P28 = (1024.0 + 256.0) * 2**20
-MFMA_PEAK_TFLOPS = {"int8": 5000.0, "fp8": 5000.0, "bf16": 2500.0}
+MFMA_PEAK_TFLOPS = {"int8": 5000.0, "fp8": 5000.0, "bf16": 2500.0, "fp16": 2500.0}
 TOKENS = 8192
 FWD_KIND, BWD_KIND = "int8", "e5m2"
 
@@ -176,17 +179,14 @@ def train_step_times(torch, steps=3):
 
 def product_kernel_rooflines(L, torch, layers, reps):
     """The product kernels alone, operands already quantized, timed by HIP events on the stream
-    they are launched on: the bf16 pipeline (backward products of the default path), the int8
-    pipeline (forward products) and the fp8 pipeline (backward products with the flag set),
-    each over the same shapes the step launches them on."""
+    they are launched on: the f16 pipeline fed from E5M2 codes (backward products of the default
+    path), the int8 pipeline (forward products) and the fp8 pipeline (backward products with the
+    flag set), each over the same shapes the step launches them on."""
     dev = "cuda:0"
     out = {}
 
     def codes(P, R):
         return torch.randint(0, 120, (P, R), dtype=torch.uint8, device=dev)
-
-    def bf(P, R):
-        return torch.randn((P, R), device=dev).to(torch.bfloat16)
 
     fwd_shapes = [(ly.M, ly.N, ly.K) for ly in layers]
     bwd_shapes = [s for ly in layers for s in ((ly.M, ly.K, ly.N), (ly.N, ly.K, ly.M))]
@@ -194,8 +194,8 @@ def product_kernel_rooflines(L, torch, layers, reps):
     # fc1's input gradient takes the 128 x 192 one): fc2's input gradient and both weight gradients
     bwd128 = [s for s in bwd_shapes if not (s[0] == TOKENS and s[1] == 768)]
     for name, shapes, make, call, need_fn, peak, kernel in (
-            ("bf16", bwd128, bf, lambda X, Z, o, ws: L.sr_gemm_bf16(X, Z, out=o, workspace=ws),
-             L.raw.sr_gemm_bf16_workspace_bytes, MFMA_PEAK_TFLOPS["bf16"], "gemm_nt_kernel<BF16Mma, 128, 128, 2, 2, 2>"),
+            ("f16", bwd128, codes, lambda X, Z, o, ws: L.sr_gemm_e5m2(X, Z, out=o, workspace=ws),
+             L.raw.sr_gemm_e5m2_workspace_bytes, MFMA_PEAK_TFLOPS["fp16"], "gemm_nt_kernel<E5M2F16Mma, 128, 128, 2, 2, 2>"),
             ("int8", fwd_shapes, codes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.INT8, Z, L.INT8, out=o, workspace=ws),
              L.raw.sr_gemm_workspace_bytes, MFMA_PEAK_TFLOPS["int8"], "gemm_nt_kernel<I8Mma, 128, ...>"),
             ("fp8", bwd_shapes, codes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.E5M2, Z, L.E5M2, out=o, workspace=ws),
@@ -318,7 +318,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int8 (i32 acc) forward; e5m2 values on the bf16 pipeline (f32 acc) backward",
+        "dtype": "int8 (i32 acc) forward; e5m2 codes widened to f16 on the f16 pipeline (f32 acc) backward",
         "data": "synthetic",
         "config": {"workload": "configs[2]: GPT-2-small MLP linears fc1 (3072x768) + fc2 (768x3072), "
                                "8192 tokens, fp32 in/out, int8 SR forward, E5M2 SR backward; per layer "
@@ -336,13 +336,14 @@ def main():
                                 "SRQ_FLAG_F8_PIPELINE)"},
         "product_kernels": rl,
     }
-    dom = rl["bf16"]
+    dom = rl["f16"]
     line["roofline"] = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["TFLOP/s"], "peak": dom["peak"],
-                        "unit": "TFLOP/s", "frac": dom["frac"], "traffic": round(TRAFFIC_BF16_PRODUCT_128),
+                        "unit": "TFLOP/s", "frac": dom["frac"], "traffic": round(TRAFFIC_F16_PRODUCT_128),
                         "note": "dominant kernel of the step by time (3 of its 6 products); 38.65 GFLOP per launch "
                                 "over the mean event-timed launch, which for the two weight-gradient launches "
-                                "includes the 6 us kernel that sums the two contraction slices; algorithmic bytes "
-                                "per launch 93.8e6, measured HBM traffic 2.7x that"}
+                                "includes the kernel that sums the three contraction slices; algorithmic bytes "
+                                "per launch %.1fe6 (operands once, result once), traffic = measured HBM bytes"
+                                % (ALGORITHMIC_F16_PRODUCT_128 / 1e6)}
     if not args.no_quantizer_sweep:
         qs = quantizer_sweep(L, synth, torch, max(5, args.steps // 5))
         line["sr_quantize"] = qs

@@ -158,6 +158,15 @@ int sr_gemm_bf16(float* out, const void* X, const void* Z, size_t P, size_t Q, s
                  float beta, void* workspace, size_t workspace_bytes, void* stream);
 size_t sr_gemm_bf16_workspace_bytes(size_t P, size_t Q, size_t R);
 
+/* The same product for two matrices of E5M2 codes, computed exactly as on the bf16 pipeline
+ * (exact products, binary32 sums) but from the one-byte codes: an E5M2 code is the high byte of
+ * the binary16 number of the same value, so the kernel widens the operands in registers and
+ * multiplies on the f16 matrix pipeline.  This is how the linear entry points multiply when both
+ * operands are E5M2 and SRQ_FLAG_F8_PIPELINE is clear.  X is P x R, Z is Q x R, R % 16 == 0. */
+int sr_gemm_e5m2(float* out, const void* X, const void* Z, size_t P, size_t Q, size_t R, float alpha,
+                 float beta, void* workspace, size_t workspace_bytes, void* stream);
+size_t sr_gemm_e5m2_workspace_bytes(size_t P, size_t Q, size_t R);
+
 /* Forward pass, Alg. 1:  Y = Q(A; qA_fwd) Q(W; qW_fwd)^T.
  * M, N, K multiples of 16.  workspace: sr_linear_workspace_bytes(SRQ_OP_FWD, M, N, K). */
 int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M,

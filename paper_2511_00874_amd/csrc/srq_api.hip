@@ -311,6 +311,30 @@ int sr_gemm_bf16(float* out, const void* X, const void* Z, size_t P, size_t Q, s
              : SRQ_ERR_HIP;
 }
 
+size_t sr_gemm_e5m2_workspace_bytes(size_t P, size_t Q, size_t R) {
+  if (P == 0 || Q == 0 || R == 0) return 0;
+  return gemm_workspace_bytes(P, Q, R, PIPE_F16C);
+}
+
+int sr_gemm_e5m2(float* out, const void* X, const void* Z, size_t P, size_t Q, size_t R, float alpha, float beta,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (!out || !X || !Z) return SRQ_ERR_NULL;
+  if (P == 0 || Q == 0 || R == 0) return SRQ_ERR_SHAPE;
+  if (!fits_u32(P) || !fits_u32(Q) || !fits_u32(R)) return SRQ_ERR_SHAPE;
+  if (R % 16) return SRQ_ERR_ALIGN;
+  if (!aligned16(out) || !aligned16(X) || !aligned16(Z)) return SRQ_ERR_ALIGN;
+  if (beta != 0.0f && beta != 1.0f) return SRQ_ERR_UNSUPPORTED;
+  if (!gemm_operands_addressable(P, Q, R, PIPE_F16C)) return SRQ_ERR_UNSUPPORTED;
+  const size_t need = gemm_workspace_bytes(P, Q, R, PIPE_F16C);
+  if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return SRQ_ERR_WORKSPACE;
+  GemmScale sc{alpha, 1.0f, 1.0f, nullptr, nullptr};
+  return launch_gemm_codes(out, static_cast<const uint8_t*>(X), SRQ_E5M2, static_cast<const uint8_t*>(Z), SRQ_E5M2,
+                           P, Q, R, R, PIPE_F16C, sc, beta == 1.0f, workspace,
+                           static_cast<hipStream_t>(stream)) == hipSuccess
+             ? SRQ_OK
+             : SRQ_ERR_HIP;
+}
+
 size_t sr_linear_workspace_bytes(int op, size_t M, size_t N, size_t K) {
   if (M == 0 || N == 0 || K == 0) return 0;
   // sized for the widest operand storage (two bytes per element), so one buffer serves every format

@@ -51,6 +51,9 @@ _lib.sr_gemm_workspace_bytes.restype = _sz
 _lib.sr_gemm_bf16.argtypes = [_vp, _vp, _vp, _sz, _sz, _sz, C.c_float, C.c_float, _vp, _sz, _vp]
 _lib.sr_gemm_bf16_workspace_bytes.argtypes = [_sz, _sz, _sz]
 _lib.sr_gemm_bf16_workspace_bytes.restype = _sz
+_lib.sr_gemm_e5m2.argtypes = _lib.sr_gemm_bf16.argtypes
+_lib.sr_gemm_e5m2_workspace_bytes.argtypes = [_sz, _sz, _sz]
+_lib.sr_gemm_e5m2_workspace_bytes.restype = _sz
 _lib.sr_linear_fwd.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _vp, _sz, _vp]
 _lib.sr_linear_bwd_data.argtypes = _lib.sr_linear_fwd.argtypes
 _lib.sr_linear_bwd_weight.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp,
@@ -66,11 +69,11 @@ _lib.sr_linear_bwd_stashed.argtypes = [_vp, _vp, _vp, C.c_int, _sz, _sz, _sz, _q
 _lib.sr_update_bf16.argtypes = [_vp, _vp, C.c_float, _sz, C.c_int, C.c_uint64, C.c_uint64, _vp]
 _lib.sr_status_string.argtypes = [C.c_int]
 _lib.sr_status_string.restype = C.c_char_p
-for _n in ("sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_linear_fwd", "sr_linear_bwd_data",
+for _n in ("sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_gemm_e5m2", "sr_linear_fwd", "sr_linear_bwd_data",
            "sr_linear_bwd_weight", "sr_linear_bwd", "sr_update_bf16", "sr_linear_fwd_stash", "sr_linear_bwd_stashed"):
     getattr(_lib, _n).restype = C.c_int
 
-EXPORTS = ["sr_absmax_scale", "sr_absmax_scales", "sr_absmax_workspace_bytes", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes", "sr_gemm_bf16", "sr_gemm_bf16_workspace_bytes",
+EXPORTS = ["sr_absmax_scale", "sr_absmax_scales", "sr_absmax_workspace_bytes", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes", "sr_gemm_bf16", "sr_gemm_bf16_workspace_bytes", "sr_gemm_e5m2", "sr_gemm_e5m2_workspace_bytes",
            "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight", "sr_linear_bwd",
            "sr_linear_workspace_bytes", "sr_linear_stash_bytes", "sr_linear_fwd_stash", "sr_linear_bwd_stashed",
            "sr_update_bf16", "sr_status_string"]
@@ -244,6 +247,21 @@ def sr_gemm_bf16(X, Z, alpha=1.0, out=None, beta=0.0, workspace=None):
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     _check(_lib.sr_gemm_bf16(_dev(out), _dev(X), _dev(Z), P, Q, R, alpha, beta,
+                             _dev(workspace) if workspace is not None else None,
+                             workspace.numel() if workspace is not None else 0, _stream()))
+    return out
+
+
+def sr_gemm_e5m2(X, Z, alpha=1.0, beta=0.0, out=None, workspace=None):
+    """out (P,Q) = alpha * X Z^T for uint8 matrices of E5M2 codes: exact products, binary32 sums."""
+    P, R = X.shape
+    Q = Z.shape[0]
+    if out is None:
+        out = torch.empty((P, Q), dtype=torch.float32, device=X.device)
+    need = _lib.sr_gemm_e5m2_workspace_bytes(P, Q, R)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    _check(_lib.sr_gemm_e5m2(_dev(out), _dev(X), _dev(Z), P, Q, R, alpha, beta,
                              _dev(workspace) if workspace is not None else None,
                              workspace.numel() if workspace is not None else 0, _stream()))
     return out

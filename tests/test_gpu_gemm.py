@@ -79,6 +79,23 @@ def test_gemm_bf16_exact_products_binary32_sums():
     check_product(got, ref, ab)
 
 
+@pytest.mark.parametrize("P,Q,R", [(200, 136, 272), (70, 90, 48), (33, 1, 16), (1040, 1100, 400), (256, 192, 8192)])
+def test_gemm_e5m2_from_codes_is_exact_like_the_bf16_form(P, Q, R):
+    # every finite E5M2 code, subnormals included: the codes widened in registers must give what
+    # the same values give as bfloat16 operands (same exact products; the binary32 sums may
+    # differ in the last bits, the two pipelines group the contraction differently)
+    say("gemm e5m2 codes", P, Q, R)
+    X, Z = _rand_codes((P, R), L.E5M2, 17), _rand_codes((Q, R), L.E5M2, 18)
+    X[0, :16] = [0x00, 0x01, 0x02, 0x03, 0x04, 0x7B, 0xFB, 0x80, 0x81, 0x83, 0x84, 0x3C, 0xBC, 0x7A, 0x05, 0x40]
+    got = L.sr_gemm_e5m2(to_dev(X), to_dev(Z), alpha=0.25).cpu().numpy()
+    ref, ab = oracle.gemm_fwd(X, L.E5M2, 0.5, Z, L.E5M2, 0.5, want_abs=True)
+    check_product(got, ref, ab)
+    Xv, Zv = oracle.decode_array(L.E5M2, X), oracle.decode_array(L.E5M2, Z)
+    same = L.sr_gemm_bf16(torch.from_numpy(Xv).to(DEV).to(torch.bfloat16), torch.from_numpy(Zv).to(DEV).to(torch.bfloat16),
+                          alpha=0.25).cpu().numpy()
+    assert np.all(np.abs(got - same) <= 2e-6 * ab)
+
+
 def test_fp8_pipeline_aligns_groups_of_eight_products_to_14_bits():
     # What the hardware does, pinned: in E4M3, 256 * 256 = 2^16 next to 1 * 1 inside one run of 8
     # contraction indices loses the 1 (bits below 2^(16-13) are dropped); in the next run of 8 it
