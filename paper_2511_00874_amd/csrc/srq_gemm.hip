@@ -370,7 +370,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = __fadd_rn(v[e], o[e]);
           }
-          *reinterpret_cast<v4f*>(dst) = v4f{v[0], v[1], v[2], v[3]};
+          // the result is not read again by this kernel: a streaming store keeps it from pushing
+          // operand panels out of the L2
+          __builtin_nontemporal_store(v4f{v[0], v[1], v[2], v[3]}, reinterpret_cast<v4f*>(dst));
         } else {
           for (int e = 0; e < 4 && q + e < g.Q; ++e) dst[e] = g.accumulate ? __fadd_rn(v[e], dst[e]) : v[e];
         }
