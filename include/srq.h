@@ -90,11 +90,16 @@ typedef struct {
                            /* blocks [counter_offset, counter_offset + ceil(n/8))            */
 } srq_quant;
 
-/* How the linear entry points multiply two operands on 8-bit float grids (E4M3 / E5M2).
- * Default (flag clear): the quantizer writes each grid value as a bfloat16 number (every E4M3 /
- * E5M2 value is one) and the product runs on the bf16 matrix pipeline: products are exact and
- * sums are accumulated in binary32, so the result equals the exact product of the quantized
- * matrices (Sec. 2.2.2) to binary32 rounding.
+/* How the linear entry points multiply two operands on 8-bit float grids (E4M3 / E5M2 and the
+ * sub-grids of E4M3).
+ * Default (flag clear): products are exact and sums are accumulated in binary32, so the result
+ * equals the exact product of the quantized matrices (Sec. 2.2.2) to binary32 rounding.  Two
+ * E5M2 operands are multiplied from their one-byte codes, widened to binary16 inside the kernel
+ * (an E5M2 code is the high byte of the binary16 number of the same value), on the f16 matrix
+ * pipeline.  For any other pair the quantizer writes each grid value as a bfloat16 number
+ * (every E4M3 / E5M2 value is one) and the product runs on the bf16 matrix pipeline.  The two
+ * pipelines group the contraction differently, so their binary32 sums can differ in the last
+ * bits.
  * With SRQ_FLAG_F8_PIPELINE set on BOTH operands' quantizers the one-byte codes go to the fp8
  * matrix pipeline at twice the rate.  That hardware adds the products of each run of 8
  * consecutive contraction indices after aligning them to the largest one and truncating to 14
@@ -188,8 +193,12 @@ int sr_linear_bwd_weight(float* dW, const void* dY, int dtypedY, const void* A, 
                          size_t workspace_bytes, void* stream);
 
 /* The whole backward pass of Alg. 2 in one call: dA and dW as the two entry points above
- * would give them with the same quantizers, bit for bit, but the output gradient is read and
- * quantized once and all three operands are quantized in one launch.
+ * would give them with the same quantizers, but the output gradient is read and quantized once
+ * and all three operands are quantized in one launch.  The results are equal bit for bit
+ * whenever the two products use the same pipeline in both forms of the call (always, except
+ * when exactly one of W, A shares the E5M2 format with dY: the stored Q(dY) then has to serve
+ * both products as bfloat16, and the E5M2 x E5M2 product differs from the separate call in the
+ * order of its binary32 sums).
  * workspace: sr_linear_workspace_bytes(SRQ_OP_BWD, M, N, K). */
 int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void* W, int dtypeW,
                   const void* A, int dtypeA, size_t M, size_t N, size_t K, const srq_quant* qdY_bwd,

@@ -178,7 +178,14 @@ def _run_layer(t, q, sample=None, beta_check=False, f8_pipeline=False):
     dA1 = L.sr_linear_bwd_data(t["dY"], t["W"], q["dY_bwd"][0], q["W_bwd"][0])
     dW1 = L.sr_linear_bwd_weight(t["dY"], t["A"], q["dY_bwd"][0], q["A_bwd"][0])
     dA2, dW2 = L.sr_linear_bwd(t["dY"], t["W"], t["A"], q["dY_bwd"][0], q["W_bwd"][0], q["A_bwd"][0])
-    assert torch.equal(dA1, dA2) and torch.equal(dW1, dW2), "fused backward differs"
+    bk = [q[n][0].kind for n in ("dY_bwd", "W_bwd", "A_bwd")]
+    if bk[0] == L.E5M2 and (bk[1] == L.E5M2) != (bk[2] == L.E5M2) and not f8_pipeline:
+        # one product is E5M2 x E5M2 (from codes when called alone), the other is not: the fused call
+        # stores Q(dY) once, as bfloat16, for both -- same exact products, other order of sums
+        for a, b in ((dA1, dA2), (dW1, dW2)):
+            assert float((a - b).abs().max()) <= 1e-5 * float(a.abs().max())
+    else:
+        assert torch.equal(dA1, dA2) and torch.equal(dW1, dW2), "fused backward differs"
     if beta_check:
         acc = dW2.clone()
         L.sr_linear_bwd(t["dY"], t["W"], t["A"], q["dY_bwd"][0], q["W_bwd"][0], q["A_bwd"][0], out_dW=acc, beta=1.0)
@@ -217,6 +224,7 @@ def test_single_layer_int8_all_five_quantizers():
     {"A_fwd": L.INT8, "W_fwd": L.INT4, "A_bwd": L.INT8, "W_bwd": L.INT8, "dY_bwd": L.INT4},
     {"A_fwd": L.E4M2, "W_fwd": L.E4M2, "A_bwd": L.E4M1, "W_bwd": L.E4M1, "dY_bwd": L.E4M0},
     {"A_fwd": L.INT4, "W_fwd": L.INT8, "A_bwd": L.E4M3, "W_bwd": L.E4M2, "dY_bwd": L.E5M2},
+    {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.E4M3, "W_bwd": L.E5M2, "dY_bwd": L.E5M2},
 ])
 def test_ragged_layer_mixed_formats(kinds):
     t = _layer(272, 144, 208, 3, std_dy=1e-3, w_bf16=True)
