@@ -4,7 +4,7 @@
 //   out[p][q] = s * sum_r val(X[p][r]) * val(Z[q][r])        X: P x R, Z: Q x R, R contiguous
 //
 // All three products of Alg. 1 / Alg. 2 have this form once the quantizer has written the
-// operands with the contraction index contiguous.  Three matrix pipelines:
+// operands with the contraction index contiguous.  Four matrix pipelines:
 //   int8 codes          v_mfma_i32_32x32x32_i8        int32 accumulators, exact
 //   E4M3/E5M2 as bf16   v_mfma_f32_32x32x16_bf16      exact products, binary32 sums
 //   E5M2 codes as f16   v_mfma_f32_32x32x16_f16       the same, from one-byte codes: an E5M2 code is the
