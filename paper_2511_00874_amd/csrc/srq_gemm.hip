@@ -45,6 +45,7 @@ struct I8Mma {
   using acc_t = v16i;
   using raw_t = v4i;
   using frag_t = v4i;
+  static constexpr bool WIDENS = false;
   static __device__ __forceinline__ frag_t expand(raw_t r) { return r; }
   static constexpr int KSTEP = 32;  // contraction bytes per MFMA
   static __device__ __forceinline__ acc_t mma(frag_t a, frag_t b, acc_t c) {
@@ -62,6 +63,7 @@ struct BF16Mma {
   using acc_t = v16f;
   using raw_t = v4i;
   using frag_t = v4i;  // 8 bfloat16
+  static constexpr bool WIDENS = false;
   static __device__ __forceinline__ frag_t expand(raw_t r) { return r; }
   static constexpr int KSTEP = 32;  // bytes: 16 elements per MFMA
   static __device__ __forceinline__ acc_t mma(frag_t a, frag_t b, acc_t c) {
@@ -79,6 +81,7 @@ struct F8Mma {
   using acc_t = v16f;
   using raw_t = v8i;
   using frag_t = v8i;
+  static constexpr bool WIDENS = false;
   static __device__ __forceinline__ frag_t expand(raw_t r) { return r; }
   static constexpr int KSTEP = 64;
   static __device__ __forceinline__ acc_t mma(frag_t a, frag_t b, acc_t c) {
@@ -98,6 +101,8 @@ struct E5M2F16Mma {
   using acc_t = v16f;
   using raw_t = v4i;   // 16 codes
   using frag_t = v8i;  // 16 halves: codes 0..7, then 8..15
+  static constexpr bool WIDENS = true;
+  static constexpr int MFMA_PER_MMA = 2, VALU_PER_EXPAND = 8;
   static constexpr int KSTEP = 32;  // 32 codes (two lane groups of 16) per sub-step
   static __device__ __forceinline__ frag_t expand(raw_t r) {
     frag_t f;
@@ -286,22 +291,60 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
     };
 #pragma unroll
     for (int ks = 0; ks < PF && ks < KSUB; ++ks) fetch(ks);
+    // the interleaved widening below keeps two widened operand sets live: it fits the register
+    // file of the 4-wave workgroups (two of them per CU), not of the 8-wave 256 x 256 one
+    constexpr bool INTERLEAVE = MMA::WIDENS && NW <= 4;
+    if constexpr (!INTERLEAVE) {
 #pragma unroll
-    for (int ks = 0; ks < KSUB; ++ks) {
-      if (ks + PF < KSUB) fetch(ks + PF);
-      __builtin_amdgcn_sched_barrier(0);
-      // operands are widened (if the pipeline needs it) only now, next to their MFMAs, so the
-      // prefetched reads above stay in flight
-      frag_t xe[TM], ze[TN];
+      for (int ks = 0; ks < KSUB; ++ks) {
+        if (ks + PF < KSUB) fetch(ks + PF);
+        __builtin_amdgcn_sched_barrier(0);
+        frag_t xe[TM], ze[TN];  // (a plain copy unless the pipeline widens its operands)
 #pragma unroll
-      for (int i = 0; i < TM; ++i) xe[i] = MMA::expand(xf[ks % (PF + 1)][i]);
+        for (int i = 0; i < TM; ++i) xe[i] = MMA::expand(xf[ks % (PF + 1)][i]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) ze[j] = MMA::expand(zf[ks % (PF + 1)][j]);
+        for (int j = 0; j < TN; ++j) ze[j] = MMA::expand(zf[ks % (PF + 1)][j]);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = MMA::mma(ze[j], xe[i], acc[i][j]);  // MFMA rows: q, columns: p
-      __builtin_amdgcn_sched_barrier(0);
+          for (int j = 0; j < TN; ++j) acc[i][j] = MMA::mma(ze[j], xe[i], acc[i][j]);  // MFMA rows: q, columns: p
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+      // Operands are widened in registers (VALU) before they are multiplied.  A wave issues in
+      // order, so widening a whole sub-step and then multiplying it would leave the matrix pipe
+      // idle during the widening: instead the operands of sub-step ks + 1 are widened while the
+      // MFMAs of sub-step ks are issued, a few VALU operations after each MFMA (the scheduling
+      // groups below pin that interleaving).
+      frag_t xe[2][TM], ze[2][TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) xe[0][i] = MMA::expand(xf[0][i]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) ze[0][j] = MMA::expand(zf[0][j]);
+#pragma unroll
+      for (int ks = 0; ks < KSUB; ++ks) {
+        if (ks + PF < KSUB) fetch(ks + PF);
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks + 1 < KSUB) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i) xe[(ks + 1) & 1][i] = MMA::expand(xf[(ks + 1) % (PF + 1)][i]);
+#pragma unroll
+          for (int j = 0; j < TN; ++j) ze[(ks + 1) & 1][j] = MMA::expand(zf[(ks + 1) % (PF + 1)][j]);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = MMA::mma(ze[ks & 1][j], xe[ks & 1][i], acc[i][j]);
+        constexpr int N_MFMA = TM * TN * MMA::MFMA_PER_MMA;
+        constexpr int N_VALU = (TM + TN) * MMA::VALU_PER_EXPAND;
+        constexpr int PER = (N_VALU + N_MFMA - 1) / N_MFMA;
+#pragma unroll
+        for (int m = 0; m < N_MFMA; ++m) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);  // then up to PER VALU operations
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   };
 
