@@ -82,7 +82,7 @@ typedef struct {
   int32_t kind;            /* srq_kind                                                       */
   int32_t round;           /* srq_round                                                      */
   float scale;             /* Delta: finite, at least 2^-100 (1/scale * 2^16 stays finite)   */
-  uint32_t flags;          /* 0, or SRQ_FLAG_F8_PIPELINE (see below)                         */
+  uint32_t flags;          /* 0, or SRQ_FLAG_F8_PIPELINE | SRQ_FLAG_COUNTER_DEV (see below)  */
   const float* scale_dev;  /* if not NULL: device pointer to the scale, read by the kernels  */
                            /* instead of `scale` (no host check is then possible)            */
   uint64_t seed;           /* Philox key                                                     */
@@ -106,7 +106,12 @@ typedef struct {
  * bits, so a product more than 2^13 times smaller than its group's largest loses low bits:
  * |error| <= 7 * 2^-13 * sum over groups of the group's largest |product| (plus binary32
  * rounding).  Integer formats ignore the flag: their products are exact in int32. */
-enum { SRQ_FLAG_F8_PIPELINE = 1 };
+enum { SRQ_FLAG_F8_PIPELINE = 1,
+       /* counter_offset holds, instead of the offset itself, the device address (8-byte aligned, not
+        * NULL) of a uint64 that holds it: the kernels read it when they run.  A launch recorded in a
+        * HIP graph can then be replayed with fresh thresholds by updating that word on the device
+        * between replays (by ceil(n/8) per tensor, as the host would advance the offset). */
+       SRQ_FLAG_COUNTER_DEV = 2 };
 
 enum { SRQ_OP_FWD = 0, SRQ_OP_BWD_DATA = 1, SRQ_OP_BWD_WEIGHT = 2, SRQ_OP_BWD = 3, SRQ_OP_FWD_STASH = 4,
        SRQ_OP_BWD_STASHED = 5 };

@@ -21,7 +21,8 @@ int check_quant(const srq_quant* q) {
   if (q->kind == SRQ_NONE) return SRQ_ERR_UNSUPPORTED;  // Delta = 0 (identity) has no code form
   if (!kind_ok(q->kind)) return SRQ_ERR_FORMAT;
   if (q->round != SRQ_SR && q->round != SRQ_RTN) return SRQ_ERR_FORMAT;
-  if (q->flags & ~(uint32_t)SRQ_FLAG_F8_PIPELINE) return SRQ_ERR_FORMAT;
+  if (q->flags & ~(uint32_t)(SRQ_FLAG_F8_PIPELINE | SRQ_FLAG_COUNTER_DEV)) return SRQ_ERR_FORMAT;
+  if ((q->flags & SRQ_FLAG_COUNTER_DEV) && (q->counter_offset == 0 || (q->counter_offset & 7u))) return SRQ_ERR_ALIGN;
   if (!q->scale_dev) {
     const float s = q->scale;
     if (!(s >= 0x1p-100f) || !std::isfinite(s)) return SRQ_ERR_FORMAT;  // the kernels use (1/s) * 2^16
@@ -29,11 +30,19 @@ int check_quant(const srq_quant* q) {
   return SRQ_OK;
 }
 
+// With SRQ_FLAG_COUNTER_DEV the counter_offset field holds the device address of the counter.
+uint64_t counter_host(const srq_quant* q) { return (q->flags & SRQ_FLAG_COUNTER_DEV) ? 0ull : q->counter_offset; }
+const uint64_t* counter_dev(const srq_quant* q) {
+  return (q->flags & SRQ_FLAG_COUNTER_DEV) ? reinterpret_cast<const uint64_t*>(static_cast<uintptr_t>(q->counter_offset))
+                                           : nullptr;
+}
+
 QuantArgs make_args(const srq_quant* q, int dtype, int store) {
   QuantArgs a;
   a.kind = q->kind; a.round = q->round; a.dtype = dtype; a.store = store;
   a.scale = q->scale; a.scale_dev = q->scale_dev;
-  a.seed = q->seed; a.counter_offset = q->counter_offset;
+  a.seed = q->seed;
+  a.counter_offset = counter_host(q); a.counter_dev = counter_dev(q);
   return a;
 }
 
@@ -67,8 +76,10 @@ QuantJob make_job(const srq_quant* q, const void* x, int dtype, size_t rows, siz
   j.rows = (uint32_t)rows; j.cols = (uint32_t)cols;
   j.kind = q->kind; j.round = q->round; j.dtype = dtype; j.store = store; j.transpose = transpose;
   j.scale = q->scale; j.scale_dev = q->scale_dev;
-  j.seed = q->seed; j.counter_offset = q->counter_offset;
+  j.seed = q->seed;
+  j.counter_offset = counter_host(q); j.counter_dev = counter_dev(q);
   j.kind2 = 0; j.round2 = SRQ_SR; j.scale2 = 1.0f; j.scale_dev2 = nullptr; j.seed2 = j.counter_offset2 = 0;
+  j.counter_dev2 = nullptr;
   j.first_block = j.nblocks = 0;
   return j;
 }
@@ -79,7 +90,8 @@ QuantJob make_dual_job(const srq_quant* q, const srq_quant* q2, const void* x, i
                        int store, uint8_t* out_t, uint8_t* out2) {
   QuantJob j = make_job(q, x, dtype, rows, cols, 1, store, out_t, out2);
   j.kind2 = q2->kind; j.round2 = q2->round; j.scale2 = q2->scale; j.scale_dev2 = q2->scale_dev;
-  j.seed2 = q2->seed; j.counter_offset2 = q2->counter_offset;
+  j.seed2 = q2->seed;
+  j.counter_offset2 = counter_host(q2); j.counter_dev2 = counter_dev(q2);
   return j;
 }
 

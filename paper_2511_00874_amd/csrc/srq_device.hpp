@@ -188,6 +188,12 @@ __device__ __forceinline__ InvScale inv_scale(float scale, const float* scale_de
   return s;
 }
 
+// First Philox block of a tensor: a host value, plus the value of a device-resident counter if
+// one is given (so that a captured launch can be replayed with fresh thresholds).
+__device__ __forceinline__ uint64_t first_block(uint64_t counter_offset, const uint64_t* counter_dev) {
+  return counter_offset + (counter_dev ? *counter_dev : 0ull);
+}
+
 // ---- groups of 8 consecutive elements (one Philox block) -----------------------------------
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

@@ -20,6 +20,7 @@ struct QuantArgs {
   float scale;
   const float* scale_dev;
   uint64_t seed, counter_offset;
+  const uint64_t* counter_dev;  // if not null: its value is added to counter_offset on the device
 };
 
 // codes: rows x cols (transpose_out = 0) or cols x rows (1).  Shapes already validated.
@@ -41,10 +42,12 @@ struct QuantJob {
   float scale;
   const float* scale_dev;
   uint64_t seed, counter_offset;
+  const uint64_t* counter_dev;   // if not null: its value is added to counter_offset on the device
   int kind2, round2;
   float scale2;
   const float* scale_dev2;
   uint64_t seed2, counter_offset2;
+  const uint64_t* counter_dev2;
   uint32_t first_block, nblocks;  // filled by the launcher
 };
 struct QuantJobs {

@@ -27,8 +27,10 @@ template <int KIND, int SRC, int ROUND, int STORE>
 __global__ __launch_bounds__(QBLOCK) void quantize_flat_kernel(uint8_t* __restrict__ out,
                                                                const void* __restrict__ x, size_t n,
                                                                float scale, const float* scale_dev, int kind,
-                                                               uint64_t seed, uint64_t counter_offset) {
+                                                               uint64_t seed, uint64_t counter_host,
+                                                               const uint64_t* counter_dev) {
   const InvScale inv = inv_scale(scale, scale_dev, kind);
+  const uint64_t counter_offset = first_block(counter_host, counter_dev);
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
   const size_t ngroups = (n + 7) / 8;
   const size_t stride = (size_t)gridDim.x * QBLOCK;
@@ -74,8 +76,10 @@ template <int KIND, int ROUND, int STORE>
 __global__ __launch_bounds__(QBLOCK) void quantize_flat_f32_kernel(uint8_t* __restrict__ out,
                                                                    const float* __restrict__ x, size_t nchunks,
                                                                    float scale, const float* scale_dev, int kind,
-                                                                   uint64_t seed, uint64_t counter_offset) {
+                                                                   uint64_t seed, uint64_t counter_host,
+                                                                   const uint64_t* counter_dev) {
   const InvScale inv = inv_scale(scale, scale_dev, kind);
+  const uint64_t counter_offset = first_block(counter_host, counter_dev);
   const uint32_t lane = threadIdx.x & 63u;
   const size_t waves = (size_t)gridDim.x * (QBLOCK / 64);
   for (size_t c = (size_t)blockIdx.x * (QBLOCK / 64) + (threadIdx.x >> 6); c < nchunks; c += waves)
@@ -92,7 +96,8 @@ constexpr int TR = 128, TC = 64;
 template <int KIND, int SRC, int ROUND, int STORE>
 __global__ __launch_bounds__(QBLOCK) void quantize_transpose_kernel(
     uint8_t* __restrict__ out, const void* __restrict__ x, uint32_t rows, uint32_t cols, float scale,
-    const float* scale_dev, int kind, uint64_t seed, uint64_t counter_offset) {
+    const float* scale_dev, int kind, uint64_t seed, uint64_t counter_host, const uint64_t* counter_dev) {
+  const uint64_t counter_offset = first_block(counter_host, counter_dev);
   // one tile element per code: a byte, or 16 bits when the grid values are stored as bfloat16
   using elem_t = typename std::conditional<STORE == STORE_BF16, uint16_t, uint8_t>::type;
   constexpr int ES = sizeof(elem_t);
@@ -306,7 +311,7 @@ hipError_t launch_one(void* codes, const void* x, size_t rows, size_t cols, int 
     dim3 grid((unsigned)((cols + TC - 1) / TC), (unsigned)((rows + TR - 1) / TR));
     quantize_transpose_kernel<KIND, SRC, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
         static_cast<uint8_t*>(codes), x, (uint32_t)rows, (uint32_t)cols, a.scale, a.scale_dev, a.kind, a.seed,
-        a.counter_offset);
+        a.counter_offset, a.counter_dev);
   } else {
     const size_t n = rows * cols;
     size_t done = 0;  // elements handled by the coalesced chunk kernel
@@ -316,7 +321,7 @@ hipError_t launch_one(void* codes, const void* x, size_t rows, size_t cols, int 
         const int grid = grid_for(nchunks, QBLOCK / 64, 1 << 22);
         quantize_flat_f32_kernel<KIND, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
             static_cast<uint8_t*>(codes), static_cast<const float*>(x), nchunks, a.scale, a.scale_dev, a.kind, a.seed,
-            a.counter_offset);
+            a.counter_offset, a.counter_dev);
         done = nchunks * CHUNK;
       }
     }
@@ -327,7 +332,7 @@ hipError_t launch_one(void* codes, const void* x, size_t rows, size_t cols, int 
       const int grid = grid_for((n - done + 7) / 8, QBLOCK * 4, 1 << 20);
       quantize_flat_kernel<KIND, SRC, ROUND, STORE><<<grid, QBLOCK, 0, stream>>>(
           static_cast<uint8_t*>(codes) + out_bytes, static_cast<const uint8_t*>(x) + done * es, n - done, a.scale,
-          a.scale_dev, a.kind, a.seed, a.counter_offset + done / 8);
+          a.scale_dev, a.kind, a.seed, a.counter_offset + done / 8, a.counter_dev);
     }
   }
   return hipGetLastError();

@@ -19,8 +19,9 @@ constexpr int FLAT_GROUPS_PER_BLOCK = QBLOCK;  // four 512-element chunks: one p
 
 template <int KIND, bool AS_BF16>
 __device__ __forceinline__ void job_quantize_group(uint32_t (&c)[8], const float (&v)[8], const InvScale& inv,
-                                                   const QuantJob& j, uint64_t g, uint32_t k0, uint32_t k1) {
-  if (j.round == SRQ_SR) quantize_group<KIND, SRQ_SR, AS_BF16>(c, v, inv, j.counter_offset + g, k0, k1);
+                                                   const QuantJob& j, uint64_t ctr, uint64_t g, uint32_t k0,
+                                                   uint32_t k1) {
+  if (j.round == SRQ_SR) quantize_group<KIND, SRQ_SR, AS_BF16>(c, v, inv, ctr + g, k0, k1);
   else quantize_group<KIND, SRQ_RTN, AS_BF16>(c, v, inv, 0, 0, 0);
 }
 
@@ -48,6 +49,7 @@ __device__ __forceinline__ void store_group(uint8_t* out, size_t base, const uin
 template <int KIND, bool AS_BF16>
 __device__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
   const InvScale inv = inv_scale(j.scale, j.scale_dev, j.kind);
+  const uint64_t ctr = first_block(j.counter_offset, j.counter_dev);
   const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
   const size_t n = (size_t)j.rows * j.cols, ngroups = n / 8;
   size_t first_group = 0;
@@ -56,9 +58,9 @@ __device__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
     const float* x = static_cast<const float*>(j.x);
     for (size_t c = (size_t)local * (QBLOCK / 64) + (threadIdx.x >> 6); c < nchunks; c += waves) {
       if (j.round == SRQ_SR)
-        quantize_chunk_f32<KIND, SRQ_SR, AS_BF16 ? 2 : 0>(j.out, x, c, threadIdx.x & 63u, inv, k0, k1, j.counter_offset);
+        quantize_chunk_f32<KIND, SRQ_SR, AS_BF16 ? 2 : 0>(j.out, x, c, threadIdx.x & 63u, inv, k0, k1, ctr);
       else
-        quantize_chunk_f32<KIND, SRQ_RTN, AS_BF16 ? 2 : 0>(j.out, x, c, threadIdx.x & 63u, inv, k0, k1, j.counter_offset);
+        quantize_chunk_f32<KIND, SRQ_RTN, AS_BF16 ? 2 : 0>(j.out, x, c, threadIdx.x & 63u, inv, k0, k1, ctr);
     }
     first_group = nchunks * (CHUNK / 8);
   }
@@ -66,7 +68,7 @@ __device__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
     float v[8];
     uint32_t c[8];
     job_load_group(v, j, g, n);
-    job_quantize_group<KIND, AS_BF16>(c, v, inv, j, g, k0, k1);
+    job_quantize_group<KIND, AS_BF16>(c, v, inv, j, ctr, g, k0, k1);
     store_group<AS_BF16>(j.out, g * 8, c);
   }
 }
@@ -81,6 +83,8 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
   elem_t* tile = reinterpret_cast<elem_t*>(smem);
   const InvScale inv = inv_scale(j.scale, j.scale_dev, j.kind);
   const InvScale inv2 = j.out2 && j.kind2 ? inv_scale(j.scale2, j.scale_dev2, j.kind2) : inv;
+  const uint64_t ctr = first_block(j.counter_offset, j.counter_dev);
+  const uint64_t ctr2 = j.out2 && j.kind2 ? first_block(j.counter_offset2, j.counter_dev2) : 0ull;
   const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
   const uint32_t tiles_x = (j.cols + TC - 1) / TC;
   const uint32_t r0 = (local / tiles_x) * TR, c0 = (local % tiles_x) * TC;
@@ -107,7 +111,7 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
       uint32_t addA[4], addB[4];
       if (j.round == SRQ_SR) {
         uint32_t w[4];
-        philox_block(j.counter_offset + (odd ? eB : eA) / 8, k0, k1, w);
+        philox_block(ctr + (odd ? eB : eA) / 8, k0, k1, w);
         const uint32_t nb0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[0], 0xB1, 0xF, 0xF, true);
         const uint32_t nb1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[1], 0xB1, 0xF, 0xF, true);
         const uint32_t nb2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[2], 0xB1, 0xF, 0xF, true);
@@ -140,7 +144,7 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
         uint32_t add2A[4], add2B[4], da[4], db[4];
         if (j.round2 == SRQ_SR) {
           uint32_t w[4];
-          philox_block(j.counter_offset2 + (odd ? eB : eA) / 8, (uint32_t)j.seed2, (uint32_t)(j.seed2 >> 32), w);
+          philox_block(ctr2 + (odd ? eB : eA) / 8, (uint32_t)j.seed2, (uint32_t)(j.seed2 >> 32), w);
           const uint32_t nb0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[0], 0xB1, 0xF, 0xF, true);
           const uint32_t nb1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[1], 0xB1, 0xF, 0xF, true);
           const uint32_t nb2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[2], 0xB1, 0xF, 0xF, true);
@@ -175,13 +179,13 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
         const size_t g = ((size_t)row * cols + col) / 8;
         float v[8];
         job_load_group(v, j, g, n);
-        job_quantize_group<KIND, AS_BF16>(c, v, inv, j, g, k0, k1);
+        job_quantize_group<KIND, AS_BF16>(c, v, inv, j, ctr, g, k0, k1);
         if (j.out2 && j.kind2 == 0) {
           store_group<AS_BF16>(j.out2, g * 8, c);
         } else if (j.out2) {
           uint32_t c2[8];
           if (j.round2 == SRQ_SR)
-            quantize_group<SRQ_INTX, SRQ_SR, false>(c2, v, inv2, j.counter_offset2 + g, (uint32_t)j.seed2,
+            quantize_group<SRQ_INTX, SRQ_SR, false>(c2, v, inv2, ctr2 + g, (uint32_t)j.seed2,
                                                     (uint32_t)(j.seed2 >> 32));
           else
             quantize_group<SRQ_INTX, SRQ_RTN, false>(c2, v, inv2, 0, 0, 0);

@@ -16,7 +16,7 @@ F32, BF16 = 0, 1
 NONE, INT8, INT4, E4M3, E5M2, E4M2, E4M1, E4M0 = 0, 1, 2, 3, 4, 5, 6, 7
 SR, RTN = 0, 1
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD, OP_FWD_STASH, OP_BWD_STASHED = 0, 1, 2, 3, 4, 5
-FLAG_F8_PIPELINE = 1
+FLAG_F8_PIPELINE, FLAG_COUNTER_DEV = 1, 2
 KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2", E4M2: "e4m2", E4M1: "e4m1", E4M0: "e4m0"}
 QMAX = {INT8: 127.0, INT4: 7.0, E4M3: 448.0, E5M2: 57344.0, E4M2: 448.0, E4M1: 384.0, E4M0: 256.0}
 
@@ -132,7 +132,13 @@ class Quant:
         else:
             q.scale, q.scale_dev = float(self.scale), None
         q.seed = self.seed & (2**64 - 1)
-        q.counter_offset = self.counter_offset & (2**64 - 1)
+        if isinstance(self.counter_offset, torch.Tensor):
+            # a 1-element int64 device tensor: the kernels read the offset when they run
+            assert self.counter_offset.dtype == torch.int64 and self.counter_offset.numel() == 1
+            q.flags |= FLAG_COUNTER_DEV
+            q.counter_offset = _dev(self.counter_offset)
+        else:
+            q.counter_offset = self.counter_offset & (2**64 - 1)
         return q
 
 
