@@ -102,6 +102,17 @@ def test_linear_argument_checks(lib):
     assert r.sr_linear_bwd_weight(*args, 64, 128, 128, C.byref(q8), C.byref(q8), 0.5, buf, ws, None) == -6
     # int32 accumulation bound: contraction longer than 2^31 / 127^2
     assert r.sr_linear_bwd_weight(*args, 133168, 16, 16, C.byref(q8), C.byref(q8), 0.0, buf, 1 << 40, None) == -6
+    # an operand matrix of 2 GiB or more (32-bit buffer offsets inside the product kernel)
+    assert r.sr_linear_fwd(*args, 1 << 20, 128, 4096, C.byref(q8), C.byref(q8), buf, 1 << 40, None) == -6
+    q52 = _q(lib, 4)
+    assert r.sr_linear_bwd(buf, buf, buf, 0, buf, 0, buf, 0, 1 << 20, 2048, 128, C.byref(q52), C.byref(q52), C.byref(q52),
+                           0.0, buf, 1 << 40, None) == -6
+    # the stash pair: integer forward formats only; a missing stash is a workspace error
+    assert r.sr_linear_fwd_stash(*args, 64, 128, 128, C.byref(qf), C.byref(qf), C.byref(q52), C.byref(q52), buf, ws, buf, ws,
+                                 None) == -6
+    assert r.sr_linear_fwd_stash(*args, 64, 128, 128, C.byref(q8), C.byref(q8), C.byref(q52), C.byref(q52), None, 0, buf, ws,
+                                 None) == -5
+    assert lib.sr_linear_stash_bytes(64, 128, 128) >= 2 * 128 * (64 + 128)
     assert r.sr_gemm_codes(buf, buf, 1, buf, 3, 16, 16, 16, 1.0, 0.0, None, 0, None) == -6
     assert r.sr_gemm_codes(buf, buf, 1, buf, 1, 16, 16, 24, 1.0, 0.0, None, 0, None) == -4
 
