@@ -228,7 +228,7 @@ def test_single_layer_int8_all_five_quantizers():
 ])
 def test_ragged_layer_mixed_formats(kinds):
     t = _layer(272, 144, 208, 3, std_dy=1e-3, w_bf16=True)
-    _run_layer(t, _quants(kinds, t, seed=5))
+    _run_layer(t, _quants(kinds, t, seed=5), beta_check=True)
 
 
 def test_gpt2_mlp_shapes_int8_forward_e5m2_backward():
