@@ -265,6 +265,19 @@ __device__ __forceinline__ void quantize_group(uint32_t (&c)[8], const float (&v
 constexpr int CHUNK = 512;
 
 // store modes: 0 one byte per element, 1 nibbles, 2 bfloat16 (values as in StoreMode)
+// Stores that write through the L2 (system-scope cache policy) without the streaming hint: the
+// line does not stay dirty in the L2 (nothing left to flush when the kernel ends) but is still
+// allocated in the last-level cache for the kernel that reads it next.
+__device__ __forceinline__ void store_through16(void* p, const u32x4& v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_through8(void* p, const u32x2& v) {
+  asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_through4(void* p, uint32_t v) {
+  asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+}
+
 template <int KIND, int ROUND, int STORE>
 __device__ __forceinline__ void quantize_chunk_f32(uint8_t* __restrict__ out, const float* __restrict__ x,
                                                    size_t chunk, uint32_t lane, const InvScale& s, uint32_t k0,
@@ -300,8 +313,9 @@ __device__ __forceinline__ void quantize_chunk_f32(uint8_t* __restrict__ out, co
     o[64] = (uint16_t)pack4_nibbles(cb);
   } else if constexpr (STORE == 2) {
     u32x2* o = reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + e0);
-    __builtin_nontemporal_store(u32x2{ca[0] | (ca[1] << 16), ca[2] | (ca[3] << 16)}, o);
-    __builtin_nontemporal_store(u32x2{cb[0] | (cb[1] << 16), cb[2] | (cb[3] << 16)}, o + 64);
+    const u32x2 va = {ca[0] | (ca[1] << 16), ca[2] | (ca[3] << 16)}, vb = {cb[0] | (cb[1] << 16), cb[2] | (cb[3] << 16)};
+    __builtin_nontemporal_store(va, o);
+    __builtin_nontemporal_store(vb, o + 64);
   } else {
     uint32_t* o = reinterpret_cast<uint32_t*>(out + e0);
     __builtin_nontemporal_store(pack4_bytes(ca), o);

@@ -398,7 +398,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
       const size_t idx = (size_t)p * g.Q + q;
       if (pbase) {
         if (q_vec) {
-          *reinterpret_cast<v4u*>(pbase + idx) = raw;
+          // write-through: nothing of the partial tile stays dirty in the L2 when the kernel
+          // ends, and the reduction launched next still finds it in the last-level cache
+          asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(pbase + idx), "v"(raw) : "memory");
         } else {
           for (int e = 0; e < 4 && q + e < g.Q; ++e) pbase[idx + e] = raw[e];
         }

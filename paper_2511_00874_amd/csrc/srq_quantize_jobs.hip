@@ -133,11 +133,11 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
       if (j.out2 && j.kind2 == 0) {
         if constexpr (AS_BF16) {
           uint16_t* o = reinterpret_cast<uint16_t*>(j.out2);
-          if (okA) *reinterpret_cast<u32x2*>(o + eA) = u32x2{ca[0] | (ca[1] << 16), ca[2] | (ca[3] << 16)};
-          if (okB) *reinterpret_cast<u32x2*>(o + eB) = u32x2{cb[0] | (cb[1] << 16), cb[2] | (cb[3] << 16)};
+          if (okA) store_through8(o + eA, u32x2{ca[0] | (ca[1] << 16), ca[2] | (ca[3] << 16)});
+          if (okB) store_through8(o + eB, u32x2{cb[0] | (cb[1] << 16), cb[2] | (cb[3] << 16)});
         } else {
-          if (okA) *reinterpret_cast<uint32_t*>(j.out2 + eA) = pack4_bytes(ca);
-          if (okB) *reinterpret_cast<uint32_t*>(j.out2 + eB) = pack4_bytes(cb);
+          if (okA) store_through4(j.out2 + eA, pack4_bytes(ca));
+          if (okB) store_through4(j.out2 + eB, pack4_bytes(cb));
         }
       } else if (j.out2) {
         // the second quantizer: its own thresholds (same pairing of lanes and Philox blocks)
@@ -159,8 +159,8 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
           quantize_quad<SRQ_INTX, SRQ_RTN, false>(da, a.x, a.y, a.z, a.w, inv2, add2A);
           quantize_quad<SRQ_INTX, SRQ_RTN, false>(db, b.x, b.y, b.z, b.w, inv2, add2B);
         }
-        if (okA) *reinterpret_cast<uint32_t*>(j.out2 + eA) = pack4_bytes(da);
-        if (okB) *reinterpret_cast<uint32_t*>(j.out2 + eB) = pack4_bytes(db);
+        if (okA) store_through4(j.out2 + eA, pack4_bytes(da));
+        if (okB) store_through4(j.out2 + eB, pack4_bytes(db));
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -207,7 +207,7 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
     elem_t* dst = reinterpret_cast<elem_t*>(j.out) + (size_t)col * rows + row;
 #pragma unroll
     for (int i = 0; i < ES; ++i)
-      reinterpret_cast<u32x4*>(dst)[i] = u32x4{src[4 * i], src[4 * i + 1], src[4 * i + 2], src[4 * i + 3]};
+      store_through16(reinterpret_cast<u32x4*>(dst) + i, u32x4{src[4 * i], src[4 * i + 1], src[4 * i + 2], src[4 * i + 3]});
   }
 }
 
