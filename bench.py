@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # contraction 768) and the two weight gradients (2.36 M outputs, contraction 8192), one-byte operands
 ALGORITHMIC_F16_PRODUCT_128 = ((8192 * 768 + 3072 * 768 + 4 * 8192 * 3072) + 2 * (3072 * 8192 + 768 * 8192 + 4 * 3072 * 768)) / 3
 # measured HBM bytes of the same three launches, slice sums included (rocprofv3 FETCH_SIZE / WRITE_SIZE)
-TRAFFIC_F16_PRODUCT_128 = (2 * (57.4 + 27.0 + 27.0 + 9.0) + (24.2 + 96.3)) / 3 * 2**20
+TRAFFIC_F16_PRODUCT_128 = (2 * (52.7 + 27.0 + 27.0 + 9.0) + (24.2 + 96.2)) / 3 * 2**20
 TRAFFIC_QUANTIZE_INT8_2P28 = (1024.0 + 256.0) * 2**20
 MFMA_PEAK_TFLOPS = {"int8": 5000.0, "fp8": 5000.0, "bf16": 2500.0, "fp16": 2500.0}
 TOKENS = 8192
