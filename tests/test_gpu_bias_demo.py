@@ -64,3 +64,39 @@ def test_weight_gradient_error_shrinks_with_batch_only_under_sr():
         assert abs(sr / np.sqrt((2 * 0.21 * 4.09 + 0.21 ** 2) / b) - 1) < 0.1
         assert abs(rtn / np.sqrt(0.09 ** 2 + 0.72 / b) - 1) < 0.1
     assert rms[L.RTN][-1] > 8 * rms[L.SR][-1]
+
+
+def test_batch_size_pays_for_bits():
+    # Remark after Lemma 3 (Sec. 4.2): the stochastic-rounding part of the gradient variance goes
+    # like Delta^2 / b, so a format with one bit less (Delta doubled) needs four times the batch,
+    # and a 4-bit output gradient next to 8-bit activations is dominated by the 4-bit operand.
+    # a, dy uniform on [-1, 1): fractions are uniform, E[p (1 - p)] = 1/6, E[x^2] = 1/3, and the
+    # error of an entry of dW / b has variance
+    #   (Da^2 / 6 * E[dy^2] + Ddy^2 / 6 * E[a^2] + Da^2 Ddy^2 / 36) / b.
+    K, N = 64, 32
+
+    def rms_error(b, kind_dy, step_dy, step_a):
+        g = torch.Generator(device=DEV).manual_seed(1000 + b)
+        A = torch.rand((b, K), device=DEV, generator=g) * 2 - 1
+        dY = torch.rand((b, N), device=DEV, generator=g) * 2 - 1
+        exact = (dY.double().T @ A.double()) / b
+        qdy = L.Quant(kind_dy, step_dy, seed=23, counter_offset=0)
+        qa = L.Quant(L.INT8, step_a, seed=23, counter_offset=1 << 30)
+        dW = L.sr_linear_bwd_weight(dY, A, qdy, qa).double() / b
+        return float(torch.sqrt(torch.mean((dW - exact) ** 2)))
+
+    def closed_form(b, step_dy, step_a):
+        return np.sqrt((step_a ** 2 / 6 / 3 + step_dy ** 2 / 6 / 3 + step_a ** 2 * step_dy ** 2 / 36) / b)
+
+    d8, d4 = 1.0 / 127, 1.0 / 7
+    got = {}
+    for b in (1024, 4096, 16384):
+        got[b] = (rms_error(b, L.INT8, d8, d8), rms_error(b, L.INT8, 2 * d8, 2 * d8), rms_error(b, L.INT4, d4, d8))
+        say("b", b, "rms error of dW/b: int8", got[b][0], "one bit less", got[b][1], "int4 dY", got[b][2])
+        assert abs(got[b][0] / closed_form(b, d8, d8) - 1) < 0.1
+        assert abs(got[b][1] / closed_form(b, 2 * d8, 2 * d8) - 1) < 0.1
+        assert abs(got[b][2] / closed_form(b, d4, d8) - 1) < 0.1
+    # one bit less at four times the batch: the same error
+    assert abs(got[4096][1] / got[1024][0] - 1) < 0.1 and abs(got[16384][1] / got[4096][0] - 1) < 0.1
+    # the 4-bit gradient costs (127 / 7)^2 / 2 = 165 times the variance of the all-8-bit layer
+    assert abs(got[4096][2] / got[4096][0] / np.sqrt(((127 / 7) ** 2 + 1) / 2) - 1) < 0.1
