@@ -2,9 +2,11 @@
 
 TEST INFRASTRUCTURE.  Only tests/, the smoke check and the benchmark's
 CPU-baseline leg import this package; the product package never does, and this
-package never imports the product.  All arithmetic lives in the C file; this
-module only marshals numpy arrays and composes the oracle's own functions in
-the order of Alg. 1 and Alg. 2.
+package never imports the product.  The arithmetic lives in the C file; this
+module marshals numpy arrays and composes the oracle's own functions in the
+order of Alg. 1 and Alg. 2.  The one exception are the products of the
+weight-only objective at the end, which are their definition written as numpy
+binary64 matrix products.
 """
 import ctypes as C
 import os
@@ -231,3 +233,36 @@ def linear_bwd_data(dY, W, qdY: Quant, qW: Quant, **kw):
 def linear_bwd_weight(dY, A, qdY: Quant, qA: Quant, **kw):
     """Alg. 2, weight-gradient product."""
     return gemm_bwd_weight(qdY(dY), qdY.kind, qdY.scale, qA(A), qA.kind, qA.scale, **kw)
+
+
+# ---- weight-only quantization (Sec. 3.2: the objective with quantized weights and full-precision
+# activations; Fig. 3).  Only W goes through Q; the other operand enters the product as it is.
+# Plain definition: a binary64 matrix product of the operand with the dequantized codes (a
+# binary32 number times a grid value is exact in binary64, and the sums of at most 2^17 such
+# products lose less than 1e-11 relatively), then one rounding of scale * sum to binary32.
+def _values64(x: np.ndarray) -> np.ndarray:
+    x, dt = _src(x)
+    if dt == BF16:
+        return (x.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return x.astype(np.float64)
+
+
+def _weight_only(X64, Wv64, scale, want_abs):
+    s = np.float64(np.float32(scale))
+    out = (s * (X64 @ Wv64)).astype(np.float32)
+    if want_abs:
+        return out, (s * (np.abs(X64) @ np.abs(Wv64))).astype(np.float32)
+    return out
+
+
+def linear_fwd_weight_only(A, W, qW: Quant, want_abs=False):
+    """Y (M,N) = A What^T with A (M,K) unquantized and W (N,K) quantized by qW."""
+    What = decode_array(qW.kind, qW(W)).astype(np.float64)
+    return _weight_only(_values64(A), What.T, qW.scale, want_abs)
+
+
+def linear_bwd_data_weight_only(dY, W, qW: Quant, want_abs=False):
+    """dA (M,K) = dY What with dY (M,N) unquantized and W (N,K) quantized by qW (the same
+    quantizer as in the forward pass gives the same What: one weight copy per mini-batch)."""
+    What = decode_array(qW.kind, qW(W)).astype(np.float64)
+    return _weight_only(_values64(dY), What, qW.scale, want_abs)
