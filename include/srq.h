@@ -64,7 +64,11 @@ typedef enum { SRQ_F32 = 0, SRQ_BF16 = 1 } srq_dtype; /* dtype of a source tenso
 /* Target grid.  INT8: two's complement, [-127,127].  INT4: [-7,7], two per byte, element 2k
  * in bits 3:0 and 2k+1 in bits 7:4 of byte k (pairs run along the contiguous dimension of
  * the output).  E4M3 / E5M2: OCP 8-bit floats (bias 7 / 15, subnormals, max 448 / 57344;
- * never Inf, NaN only from NaN input).  Any zero result is stored as +0. */
+ * never Inf, NaN only from NaN input).  Any zero result is stored as +0.
+ * SRQ_NONE (Delta = 0, the identity of Def. 1) has no code form.  It is accepted in one place:
+ * as the quantizer of the row operand of sr_linear_fwd (A) and sr_linear_bwd_data (dY), for
+ * the objective with quantized weights and full-precision activations (Sec. 3.2); the other
+ * fields of that srq_quant are then ignored.  Everywhere else it is SRQ_ERR_UNSUPPORTED. */
 typedef enum {
   SRQ_NONE = 0, SRQ_INT8 = 1, SRQ_INT4 = 2, SRQ_E4M3 = 3, SRQ_E5M2 = 4,
   /* The 4-exponent-bit formats of the paper's experiments (Sec. 5) with 2 / 1 / 0 fraction bits.
@@ -114,7 +118,7 @@ enum { SRQ_FLAG_F8_PIPELINE = 1,
        SRQ_FLAG_COUNTER_DEV = 2 };
 
 enum { SRQ_OP_FWD = 0, SRQ_OP_BWD_DATA = 1, SRQ_OP_BWD_WEIGHT = 2, SRQ_OP_BWD = 3, SRQ_OP_FWD_STASH = 4,
-       SRQ_OP_BWD_STASHED = 5 };
+       SRQ_OP_BWD_STASHED = 5, SRQ_OP_FWD_WEIGHT_ONLY = 6, SRQ_OP_BWD_DATA_WEIGHT_ONLY = 7 };
 
 /* Per-tensor scale for absmax scaling (a choice of Delta; the paper leaves Delta open):
  * *scale_out_dev = max|x_i| / Qmax(kind) over the finite elements, or 1 if that is zero.
@@ -178,12 +182,23 @@ int sr_gemm_e5m2(float* out, const void* X, const void* Z, size_t P, size_t Q, s
 size_t sr_gemm_e5m2_workspace_bytes(size_t P, size_t Q, size_t R);
 
 /* Forward pass, Alg. 1:  Y = Q(A; qA_fwd) Q(W; qW_fwd)^T.
- * M, N, K multiples of 16.  workspace: sr_linear_workspace_bytes(SRQ_OP_FWD, M, N, K). */
+ * M, N, K multiples of 16.  workspace: sr_linear_workspace_bytes(SRQ_OP_FWD, M, N, K).
+ * Weight-only objective (Sec. 3.2): with qA_fwd->kind == SRQ_NONE, Y = A Q(W; qW_fwd)^T with A
+ * as it is: every product a * w_hat is exact and the sums are accumulated in binary32 (a
+ * bfloat16 A is multiplied in place on the bf16 matrix pipeline, a binary32 A as three bfloat16
+ * planes that sum to it; a non-finite element of A makes its row of Y NaN; that pipeline takes
+ * subnormal numbers as zero, so parts of A below 2^-126 do not contribute).  W may use any
+ * format.  workspace: sr_linear_workspace_bytes(SRQ_OP_FWD_WEIGHT_ONLY, M, N, K). */
 int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M,
                   size_t N, size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd,
                   void* workspace, size_t workspace_bytes, void* stream);
 
-/* Backward pass, Alg. 2, input gradient:  dA = Q(dY; qdY_bwd) Q(W; qW_bwd). */
+/* Backward pass, Alg. 2, input gradient:  dA = Q(dY; qdY_bwd) Q(W; qW_bwd).
+ * Weight-only objective: with qdY_bwd->kind == SRQ_NONE, dA = dY Q(W; qW_bwd), computed as in
+ * sr_linear_fwd; the qW of the forward pass gives the same quantized weights (one copy per
+ * mini-batch).  workspace: sr_linear_workspace_bytes(SRQ_OP_BWD_DATA_WEIGHT_ONLY, M, N, K).
+ * (The weight gradient of that objective, dY^T A, has no quantized operand and is not part of
+ * this library.) */
 int sr_linear_bwd_data(float* dA, const void* dY, int dtypedY, const void* W, int dtypeW,
                        size_t M, size_t N, size_t K, const srq_quant* qdY_bwd,
                        const srq_quant* qW_bwd, void* workspace, size_t workspace_bytes,

@@ -194,6 +194,79 @@ int run_linear(float* out, const void* x, int dtx, size_t xr, size_t xc, int x_t
   return launch_product(out, xcodes, qx, zcodes, qz, P, Q, R, pp, beta, gws, s);
 }
 
+// Products of the weight-only objective (Sec. 3.2): out (P x Q) = x . Q(w)^T with the row operand
+// x (P x R, R contiguous, binary32 or bfloat16) taken as it is.  The bf16 matrix pipeline multiplies
+// exactly: w is written as the bfloat16 numbers of its grid values (R contiguous); a bfloat16 x is
+// used in place; a binary32 x becomes three bfloat16 planes that sum to it, side by side in each
+// row, multiplied in one launch over the contraction 3 R against [w | w | w], so the planes are
+// added inside the binary32 accumulators.
+struct WeightOnlyPlan {
+  int planes;  // 1: x is bfloat16 already; 3: binary32
+  size_t x_bytes, zcodes_bytes, z_bytes, z3_bytes, gemm_bytes;
+};
+WeightOnlyPlan plan_weight_only(int dtx, int kind_w, size_t P, size_t Q, size_t R) {
+  WeightOnlyPlan wp;
+  wp.planes = dtx == SRQ_F32 ? 3 : 1;
+  wp.x_bytes = wp.planes == 3 ? align_up(3 * P * R * 2, WS_ALIGN) : 0;
+  wp.zcodes_bytes = kind_is_int(kind_w) ? align_up(Q * R, WS_ALIGN) : 0;
+  wp.z_bytes = align_up(Q * R * 2, WS_ALIGN);
+  wp.z3_bytes = wp.planes == 3 ? align_up(3 * Q * R * 2, WS_ALIGN) : 0;
+  wp.gemm_bytes = align_up(gemm_workspace_bytes(P, Q, wp.planes * R, PIPE_BF16), WS_ALIGN);
+  return wp;
+}
+size_t weight_only_total(const WeightOnlyPlan& wp) {
+  return wp.x_bytes + wp.zcodes_bytes + wp.z_bytes + wp.z3_bytes + wp.gemm_bytes;
+}
+size_t weight_only_bytes_max(size_t P, size_t Q, size_t R) {
+  const size_t a = weight_only_total(plan_weight_only(SRQ_F32, SRQ_INT8, P, Q, R));
+  const size_t b = weight_only_total(plan_weight_only(SRQ_BF16, SRQ_INT8, P, Q, R));
+  return a > b ? a : b;
+}
+
+int run_weight_only(float* out, const void* x, int dtx, const void* w, int dtw, size_t wr, size_t wc, int w_tr,
+                    const srq_quant* qw, size_t P, size_t Q, size_t R, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+  if (!out || !x) return SRQ_ERR_NULL;
+  if (!dtype_ok(dtx)) return SRQ_ERR_FORMAT;
+  int st = check_operand(w, dtw, qw);
+  if (st != SRQ_OK) return st;
+  st = check_dims(P, Q, R);
+  if (st != SRQ_OK) return st;
+  if (!aligned16(out) || !aligned16(x)) return SRQ_ERR_ALIGN;
+  const WeightOnlyPlan wp = plan_weight_only(dtx, qw->kind, P, Q, R);
+  const size_t R3 = (size_t)wp.planes * R;  // contraction length of the launch
+  if (!fits_u32(R3) || !gemm_operands_addressable(P, Q, R3, PIPE_BF16)) return SRQ_ERR_UNSUPPORTED;
+  if (!workspace_ok(workspace, workspace_bytes, weight_only_total(wp))) return SRQ_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint8_t* xplanes = static_cast<uint8_t*>(workspace);
+  uint8_t* zcodes = xplanes + wp.x_bytes;
+  uint8_t* zvals = zcodes + wp.zcodes_bytes;
+  uint8_t* z3 = zvals + wp.z_bytes;
+  void* gws = z3 + wp.z3_bytes;
+  const bool w_int = kind_is_int(qw->kind);
+  QuantJobs jobs;
+  jobs.njobs = 1;
+  jobs.job[0] = make_job(qw, w, dtw, wr, wc, w_tr, w_int ? STORE_BYTE : STORE_BF16, w_int ? zcodes : zvals, nullptr);
+  if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  if (w_int && launch_int_codes_to_bf16(reinterpret_cast<uint16_t*>(zvals), zcodes, Q * R, s) != hipSuccess)
+    return SRQ_ERR_HIP;
+  const uint8_t* xop = static_cast<const uint8_t*>(x);
+  const uint8_t* zop = zvals;
+  if (wp.planes == 3) {
+    if (launch_split3(reinterpret_cast<uint16_t*>(xplanes), static_cast<const float*>(x), P, R, s) != hipSuccess ||
+        launch_repeat3(reinterpret_cast<uint16_t*>(z3), reinterpret_cast<const uint16_t*>(zvals), Q, R, s) != hipSuccess)
+      return SRQ_ERR_HIP;
+    xop = xplanes;
+    zop = z3;
+  }
+  const GemmScale sc{1.0f, 1.0f, qw->scale, nullptr, qw->scale_dev};
+  return launch_gemm_codes(out, xop, SRQ_E5M2, zop, SRQ_E5M2, P, Q, R3, 2 * R3, PIPE_BF16, sc, false, gws, s) == hipSuccess
+             ? SRQ_OK
+             : SRQ_ERR_HIP;
+}
+
+bool is_none(const srq_quant* q) { return q && q->kind == SRQ_NONE; }
+
 }  // namespace
 
 extern "C" {
@@ -362,6 +435,8 @@ size_t sr_linear_workspace_bytes(int op, size_t M, size_t N, size_t K) {
              align_up(gemm_workspace_bytes(N, K, M, PIPE_BF16), WS_ALIGN) +
              align_up(gemm_workspace_bytes(M, K, N, PIPE_I8), WS_ALIGN) +
              align_up(gemm_workspace_bytes(N, K, M, PIPE_I8), WS_ALIGN);
+    case SRQ_OP_FWD_WEIGHT_ONLY: return weight_only_bytes_max(M, N, K);
+    case SRQ_OP_BWD_DATA_WEIGHT_ONLY: return weight_only_bytes_max(M, K, N);
     default: return 0;
   }
 }
@@ -370,6 +445,8 @@ size_t sr_linear_workspace_bytes(int op, size_t M, size_t N, size_t K) {
 int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
                   size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd, void* workspace,
                   size_t workspace_bytes, void* stream) {
+  if (is_none(qA_fwd))  // weight-only objective: A enters as it is
+    return run_weight_only(Y, A, dtypeA, W, dtypeW, N, K, 0, qW_fwd, M, N, K, workspace, workspace_bytes, stream);
   return run_linear(Y, A, dtypeA, M, K, 0, qA_fwd, W, dtypeW, N, K, 0, qW_fwd, M, N, K, 0.0f, workspace,
                     workspace_bytes, stream);
 }
@@ -378,6 +455,8 @@ int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW
 int sr_linear_bwd_data(float* dA, const void* dY, int dtypedY, const void* W, int dtypeW, size_t M,
                        size_t N, size_t K, const srq_quant* qdY_bwd, const srq_quant* qW_bwd,
                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (is_none(qdY_bwd))  // weight-only objective: dY enters as it is
+    return run_weight_only(dA, dY, dtypedY, W, dtypeW, N, K, 1, qW_bwd, M, K, N, workspace, workspace_bytes, stream);
   return run_linear(dA, dY, dtypedY, M, N, 0, qdY_bwd, W, dtypeW, N, K, 1, qW_bwd, M, K, N, 0.0f,
                     workspace, workspace_bytes, stream);
 }

@@ -78,6 +78,13 @@ hipError_t launch_absmax_batch(AbsmaxBatch& b, hipStream_t stream);
 hipError_t launch_update_bf16(uint16_t* w, const float* g, float eta, size_t n, int round, uint64_t seed,
                               uint64_t counter_offset, hipStream_t stream);
 
+// Weight-only objective (Sec. 3.2).  split3: x (rows x cols binary32, cols % 8 == 0) as rows x 3 cols
+// bfloat16, row m = [p0 | p1 | p2] with p0 + p1 + p2 = x row m exactly.  repeat3: rows x cols bfloat16
+// -> rows x 3 cols, each row three times over.  Integer codes (n bytes, n % 8 == 0) -> bfloat16 values.
+hipError_t launch_split3(uint16_t* out, const float* x, size_t rows, size_t cols, hipStream_t stream);
+hipError_t launch_repeat3(uint16_t* out, const uint16_t* in, size_t rows, size_t cols, hipStream_t stream);
+hipError_t launch_int_codes_to_bf16(uint16_t* out, const uint8_t* codes, size_t n, hipStream_t stream);
+
 hipError_t launch_absmax_scale(float* scale_out_dev, const void* x, int dtype, size_t n, int kind,
                                hipStream_t stream);
 

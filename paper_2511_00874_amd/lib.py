@@ -16,6 +16,7 @@ F32, BF16 = 0, 1
 NONE, INT8, INT4, E4M3, E5M2, E4M2, E4M1, E4M0 = 0, 1, 2, 3, 4, 5, 6, 7
 SR, RTN = 0, 1
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD, OP_FWD_STASH, OP_BWD_STASHED = 0, 1, 2, 3, 4, 5
+OP_FWD_WEIGHT_ONLY, OP_BWD_DATA_WEIGHT_ONLY = 6, 7
 FLAG_F8_PIPELINE, FLAG_COUNTER_DEV = 1, 2
 KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2", E4M2: "e4m2", E4M1: "e4m1", E4M0: "e4m0"}
 QMAX = {INT8: 127.0, INT4: 7.0, E4M3: 448.0, E5M2: 57344.0, E4M2: 448.0, E4M1: 384.0, E4M0: 256.0}
@@ -285,24 +286,25 @@ def _ws(op, M, N, K, workspace, device):
 
 
 def sr_linear_fwd(A, W, qA, qW, out=None, workspace=None):
-    """Alg. 1: Y (M,N) = Q(A) Q(W)^T, A (M,K), W (N,K)."""
+    """Alg. 1: Y (M,N) = Q(A) Q(W)^T, A (M,K), W (N,K).  qA = Quant(NONE, 1.0): A as it is
+    (weight-only objective, Sec. 3.2)."""
     M, K = A.shape
     N = W.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=A.device)
-    ws = _ws(OP_FWD, M, N, K, workspace, A.device)
+    ws = _ws(OP_FWD_WEIGHT_ONLY if qA.kind == NONE else OP_FWD, M, N, K, workspace, A.device)
     _check(_lib.sr_linear_fwd(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K,
                               C.byref(qA.c()), C.byref(qW.c()), _dev(ws), ws.numel(), _stream()))
     return out
 
 
 def sr_linear_bwd_data(dY, W, qdY, qW, out=None, workspace=None):
-    """Alg. 2: dA (M,K) = Q(dY) Q(W), dY (M,N), W (N,K)."""
+    """Alg. 2: dA (M,K) = Q(dY) Q(W), dY (M,N), W (N,K).  qdY = Quant(NONE, 1.0): dY as it is."""
     M, N = dY.shape
     K = W.shape[1]
     if out is None:
         out = torch.empty((M, K), dtype=torch.float32, device=dY.device)
-    ws = _ws(OP_BWD_DATA, M, N, K, workspace, dY.device)
+    ws = _ws(OP_BWD_DATA_WEIGHT_ONLY if qdY.kind == NONE else OP_BWD_DATA, M, N, K, workspace, dY.device)
     _check(_lib.sr_linear_bwd_data(_dev(out), _dev(dY), _dtype(dY), _dev(W), _dtype(W), M, N, K,
                                    C.byref(qdY.c()), C.byref(qW.c()), _dev(ws), ws.numel(), _stream()))
     return out

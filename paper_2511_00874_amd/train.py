@@ -14,6 +14,7 @@ from . import lib as L
 # the widest layer used here (32000 outputs in the two-byte form).  Token chunks are independent
 # in Y and dA; dW accumulates over them (beta = 1), which is also how micro-batches accumulate.
 MAX_ROWS = 16384
+NOQ = L.Quant(L.NONE, 1.0)  # the identity quantizer of the weight-only objective
 
 
 class SRLinearFn(torch.autograd.Function):
@@ -38,10 +39,15 @@ class SRLinear(torch.nn.Module):
     fresh stream positions every call); W is held in bfloat16 and updated by Eq. 10.
 
     The weight gradient is kept by the layer (`self.dW`, float32, accumulated over backward
-    calls until `update`), not handed to autograd: the update consumes it in place."""
+    calls until `update`), not handed to autograd: the update consumes it in place.
+
+    weight_only=True is the other objective of Sec. 3.2: only the weights are quantized (to
+    `fwd_kind`, one quantized copy per forward call, used again in its backward pass), activations
+    and gradients stay in binary32; the weight gradient dY^T A then has no quantized operand and is
+    a plain matrix product."""
 
     def __init__(self, in_features, out_features, seed, fwd_kind=L.INT8, bwd_kind=L.E5M2, device="cuda:0",
-                 init_std=0.02, round_mode=L.SR):
+                 init_std=0.02, round_mode=L.SR, weight_only=False):
         super().__init__()
         self.in_features, self.out_features = in_features, out_features
         g = torch.Generator(device=device).manual_seed(seed)
@@ -52,6 +58,7 @@ class SRLinear(torch.nn.Module):
         self.kinds = {"A_fwd": fwd_kind, "W_fwd": fwd_kind, "A_bwd": bwd_kind, "W_bwd": bwd_kind, "dY_bwd": bwd_kind}
         self.scales = torch.ones(5, dtype=torch.float32, device=device)
         self.seed, self.position, self.round_mode = seed, 0, round_mode
+        self.weight_only = weight_only
         self.ws = None
 
     def _q(self, name, slot, position):
@@ -64,7 +71,37 @@ class SRLinear(torch.nn.Module):
             self.ws = torch.empty(need, dtype=torch.uint8, device=self.weight.device)
         return self.ws
 
+    def _forward_weight_only(self, a):
+        M, K = a.shape
+        N = self.out_features
+        w = self.weight
+        L.sr_absmax_scales([(w, self.kinds["W_fwd"], self.scales[1:2])])
+        self._qw = self._q("W_fwd", 1, self.position)   # the same copy serves the backward pass
+        self.position += (N * K + 7) // 8
+        y = torch.empty((M, N), dtype=torch.float32, device=a.device)
+        for r0 in range(0, M, MAX_ROWS):
+            r1 = min(M, r0 + MAX_ROWS)
+            L.sr_linear_fwd(a[r0:r1], w, NOQ, self._qw, out=y[r0:r1],
+                            workspace=self._workspace(L.OP_FWD_WEIGHT_ONLY, r1 - r0))
+        return y
+
+    def _backward_weight_only(self, dy, a):
+        M, N = dy.shape
+        da = torch.empty((M, self.in_features), dtype=torch.float32, device=dy.device)
+        for r0 in range(0, M, MAX_ROWS):
+            r1 = min(M, r0 + MAX_ROWS)
+            L.sr_linear_bwd_data(dy[r0:r1], self.weight, NOQ, self._qw, out=da[r0:r1],
+                                 workspace=self._workspace(L.OP_BWD_DATA_WEIGHT_ONLY, r1 - r0))
+        if self.have_grad:
+            self.dW.addmm_(dy.t(), a)
+        else:
+            torch.mm(dy.t(), a, out=self.dW)
+        self.have_grad = True
+        return da
+
     def _forward(self, a):
+        if self.weight_only:
+            return self._forward_weight_only(a)
         M, K = a.shape
         N = self.out_features
         w = self.weight
@@ -86,6 +123,8 @@ class SRLinear(torch.nn.Module):
         return y
 
     def _backward(self, dy, a):
+        if self.weight_only:
+            return self._backward_weight_only(dy, a)
         M, N = dy.shape
         K = self.in_features
         w = self.weight
@@ -116,15 +155,15 @@ class SRLinear(torch.nn.Module):
 
 
 class Block(torch.nn.Module):
-    def __init__(self, d, heads, seed, device):
+    def __init__(self, d, heads, seed, device, weight_only=False):
         super().__init__()
         self.heads = heads
         self.ln1 = torch.nn.LayerNorm(d, device=device)
         self.ln2 = torch.nn.LayerNorm(d, device=device)
-        self.qkv = SRLinear(d, 3 * d, seed, device=device)
-        self.proj = SRLinear(d, d, seed + 1, device=device)
-        self.fc1 = SRLinear(d, 4 * d, seed + 2, device=device)
-        self.fc2 = SRLinear(4 * d, d, seed + 3, device=device)
+        self.qkv = SRLinear(d, 3 * d, seed, device=device, weight_only=weight_only)
+        self.proj = SRLinear(d, d, seed + 1, device=device, weight_only=weight_only)
+        self.fc1 = SRLinear(d, 4 * d, seed + 2, device=device, weight_only=weight_only)
+        self.fc2 = SRLinear(4 * d, d, seed + 3, device=device, weight_only=weight_only)
 
     def forward(self, x):
         B, T, d = x.shape
@@ -137,15 +176,15 @@ class Block(torch.nn.Module):
 class Decoder(torch.nn.Module):
     """Pre-norm decoder: token + position embedding, `layers` blocks, final norm, output head."""
 
-    def __init__(self, vocab=32000, d=768, heads=12, layers=12, seq=1024, seed=1, device="cuda:0"):
+    def __init__(self, vocab=32000, d=768, heads=12, layers=12, seq=1024, seed=1, device="cuda:0", weight_only=False):
         super().__init__()
         self.tok = torch.nn.Embedding(vocab, d, device=device)
         self.pos = torch.nn.Embedding(seq, d, device=device)
         torch.nn.init.normal_(self.tok.weight, std=0.02)
         torch.nn.init.normal_(self.pos.weight, std=0.02)
-        self.blocks = torch.nn.ModuleList([Block(d, heads, seed + 10 * i, device) for i in range(layers)])
+        self.blocks = torch.nn.ModuleList([Block(d, heads, seed + 10 * i, device, weight_only) for i in range(layers)])
         self.ln = torch.nn.LayerNorm(d, device=device)
-        self.head = SRLinear(d, vocab, seed + 10 * layers, device=device)
+        self.head = SRLinear(d, vocab, seed + 10 * layers, device=device, weight_only=weight_only)
 
     def sr_linears(self):
         return [m for m in self.modules() if isinstance(m, SRLinear)]

@@ -113,6 +113,13 @@ def test_linear_argument_checks(lib):
     assert r.sr_linear_fwd_stash(*args, 64, 128, 128, C.byref(q8), C.byref(q8), C.byref(q52), C.byref(q52), None, 0, buf, ws,
                                  None) == -5
     assert lib.sr_linear_stash_bytes(64, 128, 128) >= 2 * 128 * (64 + 128)
+    # the identity quantizer: row operand of the forward and input-gradient products only
+    q0 = _q(lib, 0)
+    assert r.sr_linear_fwd(*args, 64, 128, 128, C.byref(q8), C.byref(q0), buf, ws, None) == -6
+    assert r.sr_linear_bwd_weight(*args, 64, 128, 128, C.byref(q0), C.byref(q8), 0.0, buf, ws, None) == -6
+    assert r.sr_linear_fwd(*args, 64, 128, 128, C.byref(q0), C.byref(q8), buf, 16, None) == -5
+    assert r.sr_linear_fwd(*args, 64, 128, 120, C.byref(q0), C.byref(q8), buf, ws, None) == -4
+    assert r.sr_linear_bwd_data(None, buf, 0, buf, 0, 64, 128, 128, C.byref(q0), C.byref(q8), buf, ws, None) == -1
     assert r.sr_gemm_codes(buf, buf, 1, buf, 3, 16, 16, 16, 1.0, 0.0, None, 0, None) == -6
     assert r.sr_gemm_codes(buf, buf, 1, buf, 1, 16, 16, 24, 1.0, 0.0, None, 0, None) == -4
 
@@ -124,6 +131,9 @@ def test_workspace_sizes(lib):
     assert lib.sr_linear_workspace_bytes(lib.OP_BWD_DATA, M, N, K) >= M * N + N * K
     assert lib.sr_linear_workspace_bytes(lib.OP_BWD_WEIGHT, M, N, K) >= M * N + M * K
     assert lib.sr_linear_workspace_bytes(99, M, N, K) == 0
+    # weight-only products: three bfloat16 planes of the row operand, W as codes and as bfloat16
+    assert lib.sr_linear_workspace_bytes(lib.OP_FWD_WEIGHT_ONLY, M, N, K) >= 6 * M * K + 3 * N * K
+    assert lib.sr_linear_workspace_bytes(lib.OP_BWD_DATA_WEIGHT_ONLY, M, N, K) >= 6 * M * N + 3 * N * K
     assert lib.sr_linear_workspace_bytes(lib.OP_FWD, 0, N, K) == 0
     assert lib.sr_gemm_workspace_bytes(4096, 4096, 4096) == 0          # enough tiles: no split
     assert lib.sr_gemm_workspace_bytes(256, 256, 65536) > 0            # few tiles, long contraction

@@ -105,3 +105,40 @@ def test_training_step_of_a_small_decoder_reduces_the_loss():
     assert losses[-1] < losses[0] - 0.05
     assert not torch.equal(w0, model.head.weight)
     assert train.flops_per_token(model) == 6.0 * (2 * (64 * 192 + 64 * 64 + 2 * 64 * 256) + 64 * 512)
+
+
+def test_weight_only_objective_through_autograd():
+    # Sec. 3.2: one quantized copy of W per forward call, the same in its backward pass;
+    # activations and gradients unquantized; dW is then the plain product dY^T A
+    say("weight-only autograd linear")
+    M, K, N, seed = 80, 64, 48, 31
+    layer = train.SRLinear(K, N, seed, device=DEV, weight_only=True)
+    g = torch.Generator(device=DEV).manual_seed(6)
+    x = torch.randn((M, K), device=DEV, generator=g).requires_grad_()
+    dy = torch.randn((M, N), device=DEV, generator=g) * 1e-3
+    for rep in range(2):  # the second pass accumulates dW and draws a fresh copy of W
+        if x.grad is not None:
+            x.grad = None
+        start = layer.position
+        y = layer(x)
+        y.backward(dy)
+        torch.cuda.synchronize()
+        w_bits = host_src(layer.weight)
+        oq = oracle.Quant(oracle.INT8, oracle.absmax_scale(w_bits, oracle.INT8), seed, start)
+        yr, ya = oracle.linear_fwd_weight_only(x.detach().cpu().numpy(), w_bits, oq, want_abs=True)
+        dar, daa = oracle.linear_bwd_data_weight_only(dy.cpu().numpy(), w_bits, oq, want_abs=True)
+        check_product(y.detach().cpu().numpy(), yr, ya, "Y")
+        check_product(x.grad.cpu().numpy(), dar, daa, "dA")
+        dw = (rep + 1) * (dy.double().t() @ x.detach().double())
+        assert torch.allclose(layer.dW.double(), dw, rtol=1e-4, atol=1e-6 * float(dw.abs().max()))
+        assert layer.position == start + (N * K + 7) // 8
+
+
+def test_weight_only_training_step_reduces_the_loss():
+    torch.manual_seed(0)
+    model = train.Decoder(vocab=512, d=64, heads=4, layers=2, seq=32, seed=3, device=DEV, weight_only=True)
+    ids = torch.randint(0, 512, (8, 32), device=DEV)
+    tgt = torch.roll(ids, -1, dims=1)
+    losses = [float(train.train_step(model, ids, tgt, lr=0.05, micro_batches=2)) for _ in range(12)]
+    say("weight-only losses", [round(v, 3) for v in losses])
+    assert all(np.isfinite(losses)) and losses[-1] < losses[0] - 0.05
