@@ -15,6 +15,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work; they never synchronise.
  *   - The return value is the only error channel.  On any error nothing is launched.
+ *   - Entry points may be called from several host threads at once; the library keeps no
+ *     state between calls (beyond a one-time launch configuration per kernel).  Calls that
+ *     share a workspace must be ordered by the caller (same stream, or events).
  *   - Layer shapes follow torch.nn.Linear: A is M x K (tokens x in), W is N x K (out x in),
  *     Y and dY are M x N, dA is M x K, dW is N x K.  (The paper writes A_out = A W with W
  *     as in x out; that W is the transpose of this one.)

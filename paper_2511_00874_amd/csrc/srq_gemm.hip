@@ -494,13 +494,11 @@ hipError_t launch_tile(GemmParams g, hipStream_t stream) {
   constexpr int LDS_BYTES = STAGES * (BM + BN) * BK;
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
   auto kern = &gemm_nt_kernel<MMA, BM, BN, WGM, WGN, STAGES>;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  // once per kernel (a function-local static: its initialisation is safe against concurrent
+  // first calls from several host threads)
+  static const hipError_t configured = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  if (configured != hipSuccess) return configured;
   g.tiles_p = (g.P + BM - 1) / BM;
   g.tiles_q = (g.Q + BN - 1) / BN;
   dim3 grid(((g.tiles_p * g.tiles_q * g.nsplit + 7) / 8) * 8);
