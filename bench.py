@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--no-quantizer-sweep", action="store_true")
     ap.add_argument("--train-step", action="store_true",
                     help="also time whole training steps of the small decoder at batch 8, 32 and 128")
+    ap.add_argument("--llama-sweep", action="store_true",
+                    help="also time the Llama-1B-shaped linears (bf16 weights, 4-bit output gradient, 8-bit "
+                         "elsewhere) at 4096, 16384 and 65536 tokens, with the error of dW for a 4-bit against "
+                         "an 8-bit output gradient")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB device copy (known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -51,13 +55,15 @@ def parse():
 class Layer:
     """One linear's tensors, scales, quantizers, outputs and workspaces, all preallocated."""
 
-    def __init__(self, L, synth, torch, name, M, N, K, seed, f8_flag):
+    def __init__(self, L, synth, torch, name, M, N, K, seed, f8_flag, kinds=None, w_bf16=False):
         dev = "cuda:0"
         self.name, self.M, self.N, self.K = name, M, N, K
         self.A = synth.gaussian_torch((M, K), 1.0, seed, dev)
         self.W = synth.gaussian_torch((N, K), 0.02, seed + 1, dev)
+        if w_bf16:
+            self.W = self.W.to(torch.bfloat16)
         self.dY = synth.gaussian_torch((M, N), 1e-3, seed + 2, dev)
-        kinds = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.E5M2, "W_bwd": L.E5M2, "dY_bwd": L.E5M2}
+        kinds = kinds or {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.E5M2, "W_bwd": L.E5M2, "dY_bwd": L.E5M2}
         src = {"A": self.A, "W": self.W, "dY": self.dY}
         self.scales = torch.empty(5, dtype=torch.float32, device=dev)
         self.q, self.src_of = {}, {}
@@ -175,6 +181,36 @@ def train_step_times(torch, steps=3):
                           "sr_linear_TFLOP/s": round(train.flops_per_token(model) * b * 1024 / sec / 1e12, 1)}
     del model
     torch.cuda.empty_cache()
+    return out
+
+
+def llama_sweep(L, synth, torch):
+    """Config 4: the Llama-1B-shaped linears, weights held in bfloat16, the output gradient on the
+    4-bit integer grid and the other four quantizers on the 8-bit one, whole layer step (scales,
+    quantizers, three products) by HIP events.  Per token count also the batch-for-bits figure of
+    Sec. 4.2 on the 2048 x 2048 layer: rms error of the mean gradient dW / T against the product
+    of the unquantized tensors (binary64 on the device, 256 rows of dW), with a 4-bit and with an
+    8-bit output gradient: it falls like 1 / sqrt(T) and scales with the step of the format."""
+    out = {}
+    i8 = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.INT8, "W_bwd": L.INT8}
+    for T in (4096, 16384, 65536):
+        row = {}
+        for name, N, K in (("qkvo", 2048, 2048), ("gate_up", 5632, 2048), ("down", 2048, 5632)):
+            ly = Layer(L, synth, torch, name, T, N, K, 7, 0, kinds=dict(i8, dY_bwd=L.INT4), w_bf16=True)
+            ms = event_ms(torch, lambda: ly.step(L), 10)
+            row[name] = {"us": round(ms * 1e3, 1), "TFLOP/s": round(ly.flops() / ms / 1e9, 1)}
+            if name == "qkvo":
+                exact = ly.dY[:, :256].double().t() @ ly.A.double()
+                ref = float(T)
+                err = {"int4": float((ly.dW[:256].double() - exact).pow(2).mean().sqrt()) / ref}
+                l8 = Layer(L, synth, torch, name, T, N, K, 7, 0, kinds=dict(i8, dY_bwd=L.INT8), w_bf16=True)
+                l8.step(L)
+                err["int8"] = float((l8.dW[:256].double() - exact).pow(2).mean().sqrt()) / ref
+                row["rms_error_of_dW_over_T"] = {k: float("%.3g" % v) for k, v in err.items()}
+                del l8, exact
+            del ly
+            torch.cuda.empty_cache()
+        out["T%d" % T] = row
     return out
 
 
@@ -353,6 +389,8 @@ def main():
                                       "frac": qs["int8"]["frac_of_hbm_peak"], "traffic": round(TRAFFIC_QUANTIZE_INT8_2P28)}
     if args.train_step:
         line["train_step"] = train_step_times(torch)
+    if args.llama_sweep:
+        line["llama_linears"] = llama_sweep(L, synth, torch)
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)
