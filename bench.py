@@ -167,20 +167,27 @@ def quantizer_sweep(L, synth, torch, reps):
 def train_step_times(torch, steps=3):
     """Whole training step of the 12-layer decoder (d = 768, 12 heads, vocabulary 32000, 1024
     tokens per sequence, random weights and token ids): forward, backward and the updates, every
-    linear through the SR-quantized path, weights in bfloat16 updated by Eq. 10."""
+    linear through the SR-quantized path, weights in bfloat16 updated by Eq. 10.  Also the
+    weight-only objective of Sec. 3.2 (int8 weights, binary32 activations and gradients) at the
+    smallest batch."""
     from paper_2511_00874_amd import train
-    model = train.Decoder()
-    out = {"model": "decoder 12 x 768, 12 heads, vocab 32000, seq 1024; %.1f M weights in SR linears"
-                    % (sum(m.in_features * m.out_features for m in model.sr_linears()) / 1e6)}
-    for b, micro in ((8, 1), (32, 1), (128, 4)):
-        ids = torch.randint(0, 32000, (b, 1024), device="cuda:0")
-        tgt = torch.roll(ids, -1, 1)
-        train.train_step(model, ids, tgt, 1e-3, micro)
-        sec = time_steps(torch, lambda: train.train_step(model, ids, tgt, 1e-3, micro), steps, 0)
-        out["b%d" % b] = {"ms_per_step": round(sec * 1e3, 2), "micro_batches": micro,
-                          "sr_linear_TFLOP/s": round(train.flops_per_token(model) * b * 1024 / sec / 1e12, 1)}
-    del model
-    torch.cuda.empty_cache()
+    out = {}
+    for label, weight_only, batches in (("five_quantizers", False, ((8, 1), (32, 1), (128, 4))),
+                                        ("weight_only", True, ((8, 1),))):
+        model = train.Decoder(weight_only=weight_only)
+        out["model"] = ("decoder 12 x 768, 12 heads, vocab 32000, seq 1024; %.1f M weights in SR linears"
+                        % (sum(m.in_features * m.out_features for m in model.sr_linears()) / 1e6))
+        res = {}
+        for b, micro in batches:
+            ids = torch.randint(0, 32000, (b, 1024), device="cuda:0")
+            tgt = torch.roll(ids, -1, 1)
+            train.train_step(model, ids, tgt, 1e-3, micro)
+            sec = time_steps(torch, lambda: train.train_step(model, ids, tgt, 1e-3, micro), steps, 0)
+            res["b%d" % b] = {"ms_per_step": round(sec * 1e3, 2), "micro_batches": micro,
+                              "sr_linear_TFLOP/s": round(train.flops_per_token(model) * b * 1024 / sec / 1e12, 1)}
+        out[label] = res
+        del model
+        torch.cuda.empty_cache()
     return out
 
 
