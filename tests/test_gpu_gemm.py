@@ -249,6 +249,18 @@ def test_llama_shapes_int4_gradient_bf16_weights():
         _run_layer(t, _quants(kinds, t, seed=2), sample=65536)
 
 
+def test_llama_projection_at_65536_tokens_sampled():
+    # the largest token count of the sweep: 2^27-element activations and gradients, 256 x 256 tiles
+    # for Y and dA, a 65536-long contraction for dW (int32 sums stay exact below 133143)
+    kinds = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.INT8, "W_bwd": L.INT8, "dY_bwd": L.INT4}
+    t = _layer(65536, 2048, 2048, 22, std_dy=1e-3, w_bf16=True)
+    _run_layer(t, _quants(kinds, t, seed=3), sample=16384)
+    # and the middle one with the two MLP shapes
+    for N, K in ((5632, 2048), (2048, 5632)):
+        t = _layer(16384, N, K, 23, std_dy=1e-3, w_bf16=True)
+        _run_layer(t, _quants(kinds, t, seed=4), sample=16384)
+
+
 def test_fp8_pipeline_flag_same_codes_hardware_rounding():
     # the fp8 matrix pipeline: same quantized operands, products within the hardware's bound
     kinds = {"A_fwd": L.E4M3, "W_fwd": L.E4M3, "A_bwd": L.E5M2, "W_bwd": L.E5M2, "dY_bwd": L.E5M2}
