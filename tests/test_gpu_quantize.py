@@ -159,3 +159,34 @@ def test_full_size_standalone_quantize_bit_exact(kind):
         want = oracle.pack_int4(want)
     got = got.cpu().numpy()
     assert np.array_equal(got, want)
+
+
+def test_more_than_2_to_32_elements():
+    # element indices and Philox block numbers past 32 bits: 2^32 + 2^20 elements (17 GB of
+    # binary32), checked on the slices around index 2^32 and at the end; the scale must find a
+    # maximum planted past index 2^32
+    n = (1 << 32) + (1 << 20)
+    say("2^32 + 2^20 elements: generate")
+    xd = torch.empty(n, dtype=torch.float32, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(77)
+    for i in range(0, n, 1 << 30):
+        xd[i:i + (1 << 30)].normal_(generator=g)
+    xd[(1 << 32) + 12345] = -1000.0
+    for kind in (L.INT8, L.INT4):
+        s_dev = L.sr_absmax_scale(xd, kind)
+        assert float(s_dev.item()) == float(np.float32(1000.0) / np.float32(oracle.qmax(kind)))
+        batched = torch.empty(1, device=DEV)
+        L.sr_absmax_scales([(xd, kind, batched)])
+        assert torch.equal(batched, s_dev)
+        scale = float(s_dev.item()) / 64  # a finer step than the planted maximum allows: more codes in use
+        seed, off = 9, (1 << 63) - 5         # the block counter also crosses 2^63 here
+        got = L.sr_quantize(xd, L.Quant(kind, scale, seed=seed, counter_offset=off))
+        torch.cuda.synchronize()
+        per_byte = 2 if kind == L.INT4 else 1
+        for lo, hi in (((1 << 32) - (1 << 19), (1 << 32) + (1 << 19)), (n - (1 << 20), n), (0, 1 << 16)):
+            x = xd[lo:hi].cpu().numpy()
+            want = oracle.quantize(x, kind, scale, seed, off + lo // 8)
+            if kind == L.INT4:
+                want = oracle.pack_int4(want)
+            assert np.array_equal(got[lo // per_byte:hi // per_byte].cpu().numpy(), want), (L.KIND_NAMES[kind], lo)
+        del got
