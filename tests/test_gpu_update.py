@@ -83,3 +83,27 @@ def test_update_at_the_size_of_a_large_weight_matrix():
     torch.cuda.synchronize()
     ref = oracle.update_bf16(wb, grad.cpu().numpy(), 0.1, 77, 123456789)
     assert np.array_equal(bits_of(w), ref)
+
+
+def test_update_past_2_to_32_elements():
+    # element indices past 32 bits, with a ragged tail: slices around index 2^32 and at the end
+    n = (1 << 32) + (1 << 16) + 3
+    say("update", n)
+    g = torch.Generator(device=DEV).manual_seed(5)
+    w = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    grad = torch.empty(n, dtype=torch.float32, device=DEV)
+    for i in range(0, n, 1 << 30):
+        w[i:i + (1 << 30)].normal_(std=0.02, generator=g)
+        grad[i:i + (1 << 30)].normal_(std=1e-3, generator=g)
+    slices = (((1 << 32) - (1 << 16), (1 << 32) + (1 << 16)), (n - 4099, n), (0, 1 << 12))
+    before = [bits_of(w[lo:hi]).copy() for lo, hi in slices]
+    seed, off = 3, (1 << 64) - 17  # the block counter wraps around 2^64 inside the tensor
+    L.sr_update_bf16(w, grad, 0.25, seed=seed, counter_offset=off)
+    torch.cuda.synchronize()
+    for (lo, hi), wb in zip(slices, before):
+        # a slice that starts at a multiple of 8 continues the stream at its own block
+        lo8 = lo - lo % 8
+        pad = lo - lo8
+        wb8 = bits_of(w[lo8:lo]).copy() if pad else np.empty(0, dtype=np.uint16)  # (already updated: not compared)
+        ref = oracle.update_bf16(np.concatenate([wb8, wb]), grad[lo8:hi].cpu().numpy(), 0.25, seed, (off + lo8 // 8) & (2**64 - 1))
+        assert np.array_equal(bits_of(w[lo:hi]), ref[pad:]), lo
