@@ -190,3 +190,12 @@ def test_more_than_2_to_32_elements():
                 want = oracle.pack_int4(want)
             assert np.array_equal(got[lo // per_byte:hi // per_byte].cpu().numpy(), want), (L.KIND_NAMES[kind], lo)
         del got
+    # the same tensor as 65552 x 65536, transposed output: source rows past element 2^32 are the
+    # last columns of the result
+    rows, cols = 65552, 65536
+    scale, seed, off = 0.125, 4, 1 << 50
+    got = L.sr_quantize(xd.view(rows, cols), L.Quant(L.INT8, scale, seed=seed, counter_offset=off), transpose_out=True)
+    torch.cuda.synchronize()
+    for r in (0, 65535, 65536, 65551):
+        want = oracle.quantize(xd[r * cols:(r + 1) * cols].cpu().numpy(), L.INT8, scale, seed, off + r * cols // 8)
+        assert np.array_equal(got.view(cols, rows)[:, r].cpu().numpy(), want), r
