@@ -97,7 +97,7 @@ def test_update_past_2_to_32_elements():
         grad[i:i + (1 << 30)].normal_(std=1e-3, generator=g)
     slices = (((1 << 32) - (1 << 16), (1 << 32) + (1 << 16)), (n - 4099, n), (0, 1 << 12))
     before = [bits_of(w[lo:hi]).copy() for lo, hi in slices]
-    seed, off = 3, (1 << 64) - 17  # the block counter wraps around 2^64 inside the tensor
+    seed, off = 3, (1 << 64) - 17  # the block counter wraps at 2^64 inside the tensor
     L.sr_update_bf16(w, grad, 0.25, seed=seed, counter_offset=off)
     torch.cuda.synchronize()
     for (lo, hi), wb in zip(slices, before):
