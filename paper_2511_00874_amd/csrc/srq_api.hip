@@ -154,12 +154,27 @@ bool workspace_ok(const void* ws, size_t have, size_t need) {
 }
 
 int launch_product(float* out, const uint8_t* xc, const srq_quant* qx, const uint8_t* zc, const srq_quant* qz,
-                   size_t P, size_t Q, size_t R, const ProductPlan& pp, float beta, void* gws, hipStream_t s) {
+                   size_t P, size_t Q, size_t R, const ProductPlan& pp, float beta, void* gws, hipStream_t s,
+                   const SliceSum* carry = nullptr, SliceSum* defer = nullptr) {
   GemmScale sc{1.0f, qx->scale, qz->scale, qx->scale_dev, qz->scale_dev};
   return launch_gemm_codes(out, xc, qx->kind, zc, qz->kind, P, Q, R, R * pp.es, pp.pipe, sc, beta == 1.0f, gws,
-                           s) == hipSuccess
+                           s, carry, defer) == hipSuccess
              ? SRQ_OK
              : SRQ_ERR_HIP;
+}
+
+// The two products of Alg. 2 after their operands are quantized.  The weight gradient goes first
+// and leaves the sum of its contraction slices to the launch of the input gradient, whose last
+// workgroups do it (same arithmetic as in a launch of its own, one launch fewer, and the
+// memory-bound sum runs beside the matrix work).
+int launch_backward_products(float* dA, float* dW, const uint8_t* dy_rm, const uint8_t* w_t, const uint8_t* dy_t,
+                             const uint8_t* a_t, const srq_quant* qdY, const srq_quant* qW, const srq_quant* qA,
+                             size_t M, size_t N, size_t K, const ProductPlan& pd, const ProductPlan& pw, float beta,
+                             void* gws_d, void* gws_w, hipStream_t s) {
+  SliceSum sum_w{};
+  int st = launch_product(dW, dy_t, qdY, a_t, qA, N, K, M, pw, beta, gws_w, s, nullptr, &sum_w);
+  if (st != SRQ_OK) return st;
+  return launch_product(dA, dy_rm, qdY, w_t, qW, M, K, N, pd, 0.0f, gws_d, s, &sum_w, nullptr);
 }
 
 // One product of Alg. 1 / Alg. 2: quantize both operands into the workspace (one launch) with
@@ -509,9 +524,8 @@ int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void*
   jobs.job[1] = make_job(qW_bwd, W, dtypeW, N, K, 1, store, w_t, nullptr);
   jobs.job[2] = make_job(qA_bwd, A, dtypeA, M, K, 1, store, a_t, nullptr);
   if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
-  st = launch_product(dA, dy_rm, qdY_bwd, w_t, qW_bwd, M, K, N, pd, 0.0f, gws_d, s);
-  if (st != SRQ_OK) return st;
-  return launch_product(dW, dy_t, qdY_bwd, a_t, qA_bwd, N, K, M, pw, beta, gws_w, s);
+  return launch_backward_products(dA, dW, dy_rm, w_t, dy_t, a_t, qdY_bwd, qW_bwd, qA_bwd, M, N, K, pd, pw, beta, gws_d,
+                                  gws_w, s);
 }
 
 // Eq. 10 with bfloat16 weights.
@@ -612,9 +626,8 @@ int sr_linear_bwd_stashed(float* dA, float* dW, const void* dY, int dtypedY, siz
   jobs.njobs = 1;
   jobs.job[0] = make_job(qdY_bwd, dY, dtypedY, M, N, 1, store, dy_t, dy_rm);
   if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
-  st = launch_product(dA, dy_rm, qdY_bwd, w_t, qW_bwd, M, K, N, pd, 0.0f, gws_d, s);
-  if (st != SRQ_OK) return st;
-  return launch_product(dW, dy_t, qdY_bwd, a_t, qA_bwd, N, K, M, pw, beta, gws_w, s);
+  return launch_backward_products(dA, dW, dy_rm, w_t, dy_t, a_t, qdY_bwd, qW_bwd, qA_bwd, M, N, K, pd, pw, beta, gws_d,
+                                  gws_w, s);
 }
 
 const char* sr_status_string(int status) {

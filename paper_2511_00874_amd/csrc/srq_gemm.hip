@@ -22,6 +22,8 @@
 // instruction and the MFMA operand reads (ds_read_b128, one row per lane) spread over all
 // banks.  The product is computed transposed inside the wave (Z rows as the first MFMA
 // operand) so that each lane ends up with 4 consecutive q of one p: 16-byte output stores.
+#include <type_traits>
+
 #include "srq_internal.hpp"
 
 namespace srq {
@@ -147,6 +149,45 @@ __device__ __forceinline__ float total_scale(const GemmParams& g) {
   return __fmul_rn(g.alpha, __fmul_rn(sx, sz));
 }
 
+// Fixed-order sum of the slice partials of a product (deterministic), then scale: workgroup
+// `block` of `nblocks`.  Integer partials are summed in int32, the others in binary32.
+template <bool IS_INT>
+__device__ __forceinline__ void slice_sum(const SliceSum& r, uint32_t block, uint32_t nblocks) {
+  const float sx = r.s.sx_dev ? *r.s.sx_dev : r.s.sx, sz = r.s.sz_dev ? *r.s.sz_dev : r.s.sz;
+  const float s = __fmul_rn(r.s.alpha, __fmul_rn(sx, sz));
+  auto value = [&](uint32_t bits) {
+    if constexpr (IS_INT) return (int)bits; else return __uint_as_float(bits);
+  };
+  const size_t nthreads = (size_t)nblocks * blockDim.x, tid = (size_t)block * blockDim.x + threadIdx.x;
+  if ((r.total & 3u) == 0) {
+    const size_t total4 = r.total / 4;
+    const v4u* part = reinterpret_cast<const v4u*>(r.partial);
+    v4f* out = reinterpret_cast<v4f*>(r.out);
+    for (size_t i = tid; i < total4; i += nthreads) {
+      const v4u p0 = part[i];
+      auto a0 = value(p0[0]), a1 = value(p0[1]), a2 = value(p0[2]), a3 = value(p0[3]);
+      for (uint32_t z = 1; z < r.nsplit; ++z) {
+        const v4u p = part[z * total4 + i];
+        a0 += value(p[0]); a1 += value(p[1]); a2 += value(p[2]); a3 += value(p[3]);
+      }
+      v4f v = {__fmul_rn((float)a0, s), __fmul_rn((float)a1, s), __fmul_rn((float)a2, s), __fmul_rn((float)a3, s)};
+      if (r.accumulate) {
+        const v4f o = out[i];
+        v = v4f{__fadd_rn(v[0], o[0]), __fadd_rn(v[1], o[1]), __fadd_rn(v[2], o[2]), __fadd_rn(v[3], o[3])};
+      }
+      out[i] = v;
+    }
+  } else {
+    for (size_t i = tid; i < r.total; i += nthreads) {
+      auto a = value(r.partial[i]);
+      for (uint32_t z = 1; z < r.nsplit; ++z) a += value(r.partial[z * r.total + i]);
+      float v = __fmul_rn((float)a, s);
+      if (r.accumulate) v = __fadd_rn(v, r.out[i]);
+      r.out[i] = v;
+    }
+  }
+}
+
 constexpr uint32_t OOB = 0x80000000u;  // beyond any operand (operands are < 2 GiB): loads as zero
 
 // s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, others left at max)
@@ -166,9 +207,19 @@ __device__ __forceinline__ void lds_dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
                : "memory");
 }
 
+// Besides its tiles a launch can carry the slice sum of an EARLIER product (`rider`, complete when
+// this launch starts): memory-bound work that runs beside the matrix work, in the resident slots
+// the tiles leave free and in the tail of the launch, instead of in a launch of its own.
+// Workgroups [0, gemm_blocks) multiply, the rest sum.  (Measured against this: the rider groups
+// spread through the launch, every fourth group of 8 -- slower.)
 template <class MMA, int BM, int BN, int WGM, int WGN, int STAGES>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g, SliceSum rider, uint32_t gemm_blocks) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  if (blockIdx.x >= gemm_blocks) {
+    if (rider.is_int) slice_sum<true>(rider, blockIdx.x - gemm_blocks, gridDim.x - gemm_blocks);
+    else slice_sum<false>(rider, blockIdx.x - gemm_blocks, gridDim.x - gemm_blocks);
+    return;
+  }
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile (p x q)
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -426,18 +477,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g) {
   }
 }
 
-// Fixed-order sum of the split partials (deterministic), then scale.
-template <class MMA>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams g) {
-  const size_t total = (size_t)g.P * g.Q;
-  const float s = total_scale(g);
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-    auto a = MMA::from_bits(g.partial[i]);
-    for (uint32_t z = 1; z < g.nsplit; ++z) a += MMA::from_bits(g.partial[z * total + i]);
-    float v = __fmul_rn(MMA::to_f32(a), s);
-    if (g.accumulate) v = __fadd_rn(v, g.out[i]);
-    g.out[i] = v;
-  }
+// The slice sum in a launch of its own.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(SliceSum r) {
+  if (r.is_int) slice_sum<true>(r, blockIdx.x, gridDim.x);
+  else slice_sum<false>(r, blockIdx.x, gridDim.x);
 }
 
 struct Plan {
@@ -489,8 +532,24 @@ Plan make_plan(size_t P, size_t Q, size_t row_bytes) {
   return pl;
 }
 
+// What a launch is asked to do about slice sums: carry the one of an earlier product (`carry`,
+// may be null or empty), and either run its own afterwards or hand it to the caller (`defer`).
+struct SliceSumPlan {
+  const SliceSum* carry;
+  SliceSum* defer;
+};
+
+// per_thread elements per thread where the vector path applies (a launch of its own wants many
+// small workgroups, riders few and fat ones: each holds a tile's slot), at most 4096 workgroups
+uint32_t slice_sum_blocks(const SliceSum& r, uint32_t threads, uint32_t per_thread) {
+  const size_t per_block = (size_t)threads * ((r.total & 3u) == 0 ? per_thread : 1);
+  size_t blocks = (r.total + per_block - 1) / per_block;
+  if (blocks > 4096) blocks = 4096;
+  return (uint32_t)(blocks < 1 ? 1 : blocks);
+}
+
 template <class MMA, int BM, int BN, int WGM, int WGN, int STAGES>
-hipError_t launch_tile(GemmParams g, hipStream_t stream) {
+hipError_t launch_tile(GemmParams g, const SliceSumPlan& ss, hipStream_t stream) {
   constexpr int LDS_BYTES = STAGES * (BM + BN) * BK;
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
   auto kern = &gemm_nt_kernel<MMA, BM, BN, WGM, WGN, STAGES>;
@@ -501,26 +560,38 @@ hipError_t launch_tile(GemmParams g, hipStream_t stream) {
   if (configured != hipSuccess) return configured;
   g.tiles_p = (g.P + BM - 1) / BM;
   g.tiles_q = (g.Q + BN - 1) / BN;
-  dim3 grid(((g.tiles_p * g.tiles_q * g.nsplit + 7) / 8) * 8);
-  kern<<<grid, WGM * WGN * 64, LDS_BYTES, stream>>>(g);
+  const uint32_t gemm_blocks = ((g.tiles_p * g.tiles_q * g.nsplit + 7) / 8) * 8;
+  SliceSum carry{};
+  uint32_t carry_blocks = 0;
+  if (ss.carry && ss.carry->total > 0) {
+    carry = *ss.carry;
+    carry_blocks = slice_sum_blocks(carry, WGM * WGN * 64, 16);
+  }
+  kern<<<dim3(gemm_blocks + carry_blocks), WGM * WGN * 64, LDS_BYTES, stream>>>(g, carry, gemm_blocks);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  SliceSum own{};
   if (g.nsplit > 1) {
-    const size_t total = (size_t)g.P * g.Q;
-    size_t blocks = (total + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    splitk_reduce_kernel<MMA><<<(unsigned)blocks, 256, 0, stream>>>(g);
+    own.partial = g.partial; own.out = g.out; own.nsplit = g.nsplit; own.total = (size_t)g.P * g.Q;
+    own.s = GemmScale{g.alpha, g.sx, g.sz, g.sx_dev, g.sz_dev};
+    own.accumulate = g.accumulate;
+    own.is_int = std::is_same<typename MMA::acc_t, v16i>::value ? 1 : 0;
+  }
+  if (ss.defer) {
+    *ss.defer = own;
+  } else if (own.total > 0) {
+    splitk_reduce_kernel<<<slice_sum_blocks(own, 256, 4), 256, 0, stream>>>(own);
     e = hipGetLastError();
   }
   return e;
 }
 
 template <class MMA>
-hipError_t launch_mma(const GemmParams& g, const Plan& pl, hipStream_t stream) {
-  if (pl.tile == 0) return launch_tile<MMA, 256, 256, 2, 4, 2>(g, stream);  // 8 waves of 128 x 64
-  if (pl.tile == 1) return launch_tile<MMA, 128, 128, 2, 2, 2>(g, stream);  // 4 waves of 64 x 64
-  if (pl.tile == 3) return launch_tile<MMA, 128, 192, 2, 2, 2>(g, stream);  // 4 waves of 64 x 96
-  return launch_tile<MMA, 64, 64, 2, 2, 3>(g, stream);
+hipError_t launch_mma(const GemmParams& g, const Plan& pl, const SliceSumPlan& ss, hipStream_t stream) {
+  if (pl.tile == 0) return launch_tile<MMA, 256, 256, 2, 4, 2>(g, ss, stream);  // 8 waves of 128 x 64
+  if (pl.tile == 1) return launch_tile<MMA, 128, 128, 2, 2, 2>(g, ss, stream);  // 4 waves of 64 x 64
+  if (pl.tile == 3) return launch_tile<MMA, 128, 192, 2, 2, 2>(g, ss, stream);  // 4 waves of 64 x 96
+  return launch_tile<MMA, 64, 64, 2, 2, 3>(g, ss, stream);
 }
 
 }  // namespace
@@ -537,7 +608,9 @@ bool gemm_operands_addressable(size_t P, size_t Q, size_t R, int pipe) {
 
 hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint8_t* Z, int kindZ,
                              size_t P, size_t Q, size_t R, size_t pitch, int pipe, const GemmScale& s,
-                             bool accumulate, void* workspace, hipStream_t stream) {
+                             bool accumulate, void* workspace, hipStream_t stream, const SliceSum* carry,
+                             SliceSum* defer) {
+  const SliceSumPlan ss{carry, defer};
   const size_t row_bytes = pipe == PIPE_BF16 ? 2 * R : R;
   const Plan pl = make_plan(P, Q, row_bytes);
   GemmParams g;
@@ -551,15 +624,21 @@ hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint
   g.tiles_p = g.tiles_q = 0;
   g.alpha = s.alpha; g.sx = s.sx; g.sz = s.sz; g.sx_dev = s.sx_dev; g.sz_dev = s.sz_dev;
   g.accumulate = accumulate ? 1 : 0;
-  if (pipe == PIPE_I8) return launch_mma<I8Mma>(g, pl, stream);
-  if (pipe == PIPE_BF16) return launch_mma<BF16Mma>(g, pl, stream);
-  if (pipe == PIPE_F16C) return launch_mma<E5M2F16Mma>(g, pl, stream);
+  if (pipe == PIPE_I8) return launch_mma<I8Mma>(g, pl, ss, stream);
+  if (pipe == PIPE_BF16) return launch_mma<BF16Mma>(g, pl, ss, stream);
+  if (pipe == PIPE_F16C) return launch_mma<E5M2F16Mma>(g, pl, ss, stream);
   // the Z operand is the first MFMA operand, X the second
   const int fx = kindX == SRQ_E5M2, fz = kindZ == SRQ_E5M2;
-  if (!fz && !fx) return launch_mma<F8Mma<0, 0>>(g, pl, stream);
-  if (!fz && fx) return launch_mma<F8Mma<0, 1>>(g, pl, stream);
-  if (fz && !fx) return launch_mma<F8Mma<1, 0>>(g, pl, stream);
-  return launch_mma<F8Mma<1, 1>>(g, pl, stream);
+  if (!fz && !fx) return launch_mma<F8Mma<0, 0>>(g, pl, ss, stream);
+  if (!fz && fx) return launch_mma<F8Mma<0, 1>>(g, pl, ss, stream);
+  if (fz && !fx) return launch_mma<F8Mma<1, 0>>(g, pl, ss, stream);
+  return launch_mma<F8Mma<1, 1>>(g, pl, ss, stream);
+}
+
+hipError_t launch_slice_sum(const SliceSum& r, hipStream_t stream) {
+  if (r.total == 0) return hipSuccess;
+  splitk_reduce_kernel<<<slice_sum_blocks(r, 256, 4), 256, 0, stream>>>(r);
+  return hipGetLastError();
 }
 
 }  // namespace srq

@@ -110,9 +110,24 @@ size_t gemm_workspace_bytes(size_t P, size_t Q, size_t R, int pipe);
 // operand matrices must stay below 2 GiB (32-bit buffer offsets with an out-of-range sentinel)
 bool gemm_operands_addressable(size_t P, size_t Q, size_t R, int pipe);
 // pitch: bytes between consecutive operand rows (both operands), >= the row length.
+// The sum of the contraction slices of a product (fixed order, then scale): run by the product's
+// own launcher, or left to the caller (`defer`) who hands it to a LATER product launch (`carry`)
+// whose last workgroups then do it -- memory-bound work beside the tiles of an unrelated product
+// instead of a launch of its own.  total == 0: nothing to sum.
+struct SliceSum {
+  const uint32_t* partial;  // nsplit x total raw accumulators
+  float* out;
+  uint32_t nsplit;
+  size_t total;
+  GemmScale s;
+  int accumulate, is_int;
+};
 hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint8_t* Z, int kindZ,
                              size_t P, size_t Q, size_t R, size_t pitch, int pipe, const GemmScale& s,
-                             bool accumulate, void* workspace, hipStream_t stream);
+                             bool accumulate, void* workspace, hipStream_t stream,
+                             const SliceSum* carry = nullptr, SliceSum* defer = nullptr);
+// a deferred slice sum that found no later launch to ride on
+hipError_t launch_slice_sum(const SliceSum& r, hipStream_t stream);
 
 inline bool kind_is_int(int k) { return k == SRQ_INT8 || k == SRQ_INT4; }
 // 8-bit float codes: E4M3, E5M2 and the sub-grids of E4M3 (stored as E4M3 codes)
