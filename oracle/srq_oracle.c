@@ -337,7 +337,11 @@ void srq_oracle_unpack_int4(uint8_t* codes, const uint8_t* packed, size_t n) {
   }
 }
 
-/* Per-tensor scale = max|x| / Qmax over the finite elements; 1 if that is 0. */
+/* Per-tensor scale = max|x| / Qmax over the finite elements; 1 if that is 0.  The paper leaves
+ * Delta open; this choice of it is floored at 2^-100, the smallest step the quantizer accepts
+ * (below it 1 / Delta scaled by 2^16 leaves binary32): a tensor of vanishing values, such as an
+ * underflowing gradient, is then quantized on the grid of step 2^-100 (to zeros, or to its
+ * nearest neighbours), not saturated. */
 float srq_oracle_absmax_scale(const void* x, int src_dtype, size_t n, int kind) {
   float amax = 0.0f;
   for (size_t i = 0; i < n; ++i) {
@@ -345,7 +349,8 @@ float srq_oracle_absmax_scale(const void* x, int src_dtype, size_t n, int kind) 
     if (isfinite(a) && a > amax) amax = a;
   }
   if (amax == 0.0f) return 1.0f;
-  return amax / srq_oracle_qmax(kind);
+  float s = amax / srq_oracle_qmax(kind);
+  return s < 0x1p-100f ? 0x1p-100f : s;
 }
 
 /* ------------------------------------------------------------------ */

@@ -369,6 +369,30 @@ def test_absmax_scale(kind):
     assert abs(oracle.decode(kind, int(codes[np.argmax(np.abs(x))]))) >= oracle.qmax(kind) * 0.87
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_absmax_scale_has_a_floor(kind):
+    # max|x| / Qmax below 2^-100 would make 2^16 / scale overflow binary32: the step is floored
+    # there, and Eq. 1 on that grid sends 2^-120 (2^-20 of a step; for the float grids 2^-11 of the
+    # subnormal spacing at most) to zero for every one of the 65536 thresholds but never to Qmax
+    x = np.full(64, 2.0 ** -120, dtype=np.float32)
+    x[1::2] *= -1
+    assert oracle.absmax_scale(x, kind) == 2.0 ** -100
+    # just above the floor nothing changes
+    y = np.full(8, 2.0 ** -80, dtype=np.float32)
+    assert oracle.absmax_scale(y, kind) == float(np.float32(2.0 ** -80) / np.float32(oracle.qmax(kind)))
+    for r16 in (0, 1, 65535):
+        for v in (x[0], x[1]):
+            code = oracle.quantize_one(float(v), 1.0 / 2.0 ** -100, kind, (r16 + 0.5) / 65536)
+            got = oracle.decode(kind, code)
+            # the two grid neighbours of 2^-20 of a step: zero and one spacing (the smallest
+            # subnormal for the float grids), never anything near Qmax
+            spacing = {INT8: 1.0, INT4: 1.0, oracle.E4M3: 2.0 ** -9, oracle.E5M2: 2.0 ** -16, oracle.E4M2: 2.0 ** -8,
+                       oracle.E4M1: 2.0 ** -7, oracle.E4M0: 2.0 ** -6}[kind]
+            assert got in (0.0, np.sign(v) * spacing), (kind, r16, v, got)
+            if kind in (INT8, INT4):
+                assert got == 0.0  # frac = 2^-20 (or 1 - 2^-20): below (above) every threshold
+
+
 def test_bf16_source_is_widened_exactly():
     from paper_2511_00874_amd import synth
     x = synth.gaussian((257,), 0.02, 3)
