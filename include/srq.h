@@ -14,7 +14,9 @@
  *     allocates, frees or keeps them.  Tensors are dense row-major.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work; they never synchronise.
- *   - The return value is the only error channel.  On any error nothing is launched.
+ *   - The return value is the only error channel.  Argument errors are found before anything is
+ *     launched.  SRQ_ERR_HIP (the runtime refused a launch) can come after earlier launches of
+ *     the same call were enqueued; the outputs are then unspecified.
  *   - Entry points may be called from several host threads at once; the library keeps no
  *     state between calls (beyond a one-time launch configuration per kernel).  Calls that
  *     share a workspace must be ordered by the caller (same stream, or events).
@@ -124,7 +126,9 @@ enum { SRQ_OP_FWD = 0, SRQ_OP_BWD_DATA = 1, SRQ_OP_BWD_WEIGHT = 2, SRQ_OP_BWD = 
        SRQ_OP_BWD_STASHED = 5, SRQ_OP_FWD_WEIGHT_ONLY = 6, SRQ_OP_BWD_DATA_WEIGHT_ONLY = 7 };
 
 /* Per-tensor scale for absmax scaling (a choice of Delta; the paper leaves Delta open):
- * *scale_out_dev = max|x_i| / Qmax(kind) over the finite elements, or 1 if that is zero.
+ * *scale_out_dev = max|x_i| / Qmax(kind) over the finite elements, or 1 if that is zero, and
+ * never below 2^-100, the smallest step the quantizer takes (a tensor of vanishing values is
+ * then quantized on that grid, mostly to zero, instead of being saturated).
  * x: device, n elements of `dtype`, 16-byte aligned.  n may be 0 (result 1). */
 int sr_absmax_scale(float* scale_out_dev, const void* x, int dtype, size_t n, int kind,
                     void* stream);

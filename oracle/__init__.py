@@ -266,3 +266,15 @@ def linear_bwd_data_weight_only(dY, W, qW: Quant, want_abs=False):
     quantizer as in the forward pass gives the same What: one weight copy per mini-batch)."""
     What = decode_array(qW.kind, qW(W)).astype(np.float64)
     return _weight_only(_values64(dY), What, qW.scale, want_abs)
+
+
+# ---- the estimator for the quantization-aware objective (Sec. 3.3, Fig. 3).  The forward pass
+# multiplies the unquantized activation by What = Q(W; eps_W); the backward pass uses that SAME
+# What (the weight thresholds carry no pass index: one copy per mini-batch) and stochastically
+# rounds the saved activation and the output gradient.  A composition of the functions above.
+def qat_pass(A, W, dY, qW: Quant, qA_bwd: Quant, qdY_bwd: Quant, want_abs=False):
+    """(Y, dA, dW) with Y = A What^T, dA = dYhat What, dW = dYhat^T Ahat."""
+    Y = linear_fwd_weight_only(A, W, qW, want_abs=want_abs)
+    dA = linear_bwd_data(dY, W, qdY_bwd, qW, want_abs=want_abs)
+    dW = linear_bwd_weight(dY, A, qdY_bwd, qA_bwd, want_abs=want_abs)
+    return Y, dA, dW

@@ -174,7 +174,11 @@ int launch_backward_products(float* dA, float* dW, const uint8_t* dy_rm, const u
   SliceSum sum_w{};
   int st = launch_product(dW, dy_t, qdY, a_t, qA, N, K, M, pw, beta, gws_w, s, nullptr, &sum_w);
   if (st != SRQ_OK) return st;
-  return launch_product(dA, dy_rm, qdY, w_t, qW, M, K, N, pd, 0.0f, gws_d, s, &sum_w, nullptr);
+  st = launch_product(dA, dy_rm, qdY, w_t, qW, M, K, N, pd, 0.0f, gws_d, s, &sum_w, nullptr);
+  // the weight gradient is already enqueued: if the launch that was to carry its slice sum
+  // failed, finish it in a launch of its own so that dW is whole whatever happens to dA
+  if (st != SRQ_OK) (void)launch_slice_sum(sum_w, s);
+  return st;
 }
 
 // One product of Alg. 1 / Alg. 2: quantize both operands into the workspace (one launch) with

@@ -200,6 +200,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 // lane; out of range reads as zero) to LDS address `lds_addr` + lane * 16.  Written as inline
 // assembly so that the compiler does not serialise the ring of stages behind vmcnt(0): the
 // kernel counts outstanding DMAs itself (wait_vmcnt).
+// M0 (the LDS base of the DMA) is written inside the asm.  It is a reserved register: the compiler
+// neither allocates it nor honours it in a clobber list, and it writes M0 itself only for
+// constructs this file does not contain (dynamic register indexing, messages, GWS, LDS-direct
+// reads).  In the assembly generated for this file every write of m0 is the one below.
 __device__ __forceinline__ void lds_dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t lds_addr, uint32_t voff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :

@@ -214,6 +214,10 @@ __device__ __forceinline__ uint32_t absmax_slice(const void* __restrict__ x, siz
   return m;
 }
 
+// The smallest step the quantizer takes (2^16 / step must stay finite in binary32): the absmax
+// scale of a tensor of vanishing values is floored here instead of saturating every element.
+constexpr float MIN_SCALE = 0x1p-100f;
+
 __global__ void absmax_init_kernel(uint32_t* acc) { *acc = 0u; }
 
 template <int SRC>
@@ -234,7 +238,7 @@ __global__ __launch_bounds__(QBLOCK) void absmax_kernel(uint32_t* __restrict__ a
 
 __global__ void absmax_finish_kernel(float* scale, float qmax) {
   const float amax = *scale;  // the accumulator holds the bits of max|x|
-  *scale = amax == 0.0f ? 1.0f : __fdiv_rn(amax, qmax);
+  *scale = amax == 0.0f ? 1.0f : fmaxf(__fdiv_rn(amax, qmax), MIN_SCALE);
 }
 
 // ---- several tensors, several scales, two launches -----------------------------------------
@@ -282,7 +286,7 @@ __global__ __launch_bounds__(QBLOCK) void absmax_multi_finish_kernel(AbsmaxBatch
   }
   if ((int)threadIdx.x < b.nouts) {
     const float amax = __uint_as_float(tmax[b.out_tensor[threadIdx.x]]);
-    *b.out[threadIdx.x] = amax == 0.0f ? 1.0f : __fdiv_rn(amax, b.out_qmax[threadIdx.x]);
+    *b.out[threadIdx.x] = amax == 0.0f ? 1.0f : fmaxf(__fdiv_rn(amax, b.out_qmax[threadIdx.x]), MIN_SCALE);
   }
 }
 

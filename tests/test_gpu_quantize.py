@@ -105,6 +105,23 @@ def test_absmax_scale_and_device_scale_path(kind, bf16):
     assert np.array_equal(got, got2)
 
 
+@pytest.mark.parametrize("kind", [L.INT8, L.E5M2, L.E4M3])
+def test_vanishing_tensor_gets_the_floored_scale_not_saturation(kind):
+    # max|x| / Qmax below 2^-100: both absmax entry points floor the step there, and the codes
+    # quantized with that device-resident scale are the oracle's (zeros and nearest neighbours)
+    x = synth.gaussian((4096,), 2.0 ** -118, 7).astype(np.float32)
+    xd = to_dev(x)
+    want = oracle.absmax_scale(x, kind)
+    assert want == 2.0 ** -100
+    s1 = L.sr_absmax_scale(xd, kind)
+    s2 = torch.empty(1, device=DEV)
+    L.sr_absmax_scales([(xd, kind, s2)])
+    assert float(s1.item()) == want and float(s2.item()) == want
+    got = L.sr_quantize(xd, L.Quant(kind, s1, seed=4)).cpu().numpy()
+    assert np.array_equal(got, oracle_codes(xd, kind, want, 4, 0))
+    assert np.abs(oracle.decode_array(kind, got)).max() <= 1.0   # nowhere near Qmax
+
+
 def test_batched_absmax_shares_passes_and_matches_oracle():
     A = to_dev(synth.gaussian((512, 96), 1.0, 1))
     W = to_dev(synth.gaussian((64, 96), 0.02, 2), bf16=True)

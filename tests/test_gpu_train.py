@@ -142,3 +142,82 @@ def test_weight_only_training_step_reduces_the_loss():
     losses = [float(train.train_step(model, ids, tgt, lr=0.05, micro_batches=2)) for _ in range(12)]
     say("weight-only losses", [round(v, 3) for v in losses])
     assert all(np.isfinite(losses)) and losses[-1] < losses[0] - 0.05
+
+
+def test_second_forward_before_the_first_backward_keeps_the_first_calls_state():
+    # forward(x1), forward(x2), then backward of the first: its gradients must be those of a run
+    # in which nothing happened between its two passes (positions, scales and the weight
+    # quantizer of a call live on its autograd context, not on the layer)
+    K, N, seed = 64, 48, 13
+    g = torch.Generator(device=DEV).manual_seed(2)
+    x1 = torch.randn((32, K), device=DEV, generator=g)
+    x2 = torch.randn((48, K), device=DEV, generator=g) * 30.0   # another scale altogether
+    dy1 = torch.randn((32, N), device=DEV, generator=g) * 1e-3
+    ref_layer = train.SRLinear(K, N, seed, device=DEV)
+    xr = x1.clone().requires_grad_()
+    ref_layer(xr).backward(dy1)
+    torch.cuda.synchronize()
+    layer = train.SRLinear(K, N, seed, device=DEV)
+    xa = x1.clone().requires_grad_()
+    ya = layer(xa)
+    with torch.no_grad():
+        layer(x2)                       # an evaluation pass in between
+    xb = x2.clone().requires_grad_()
+    layer(xb)                           # and a second recorded forward
+    # the first call's dY draws its stream position at backward time: put the reference there
+    between = layer.position
+    ref_end = ref_layer.position
+    ya.backward(dy1)
+    torch.cuda.synchronize()
+    # A_bwd and W_bwd codes are those of the undisturbed run; only dY's position differs, so
+    # compare against the oracle at the positions this call recorded
+    M = 32
+    ab, wb = (M * K + 7) // 8, (N * K + 7) // 8
+    a_np, w_bits, dy_np = x1.cpu().numpy(), host_src(layer.weight), dy1.cpu().numpy()
+    bk = oracle.E5M2
+    qdy = oracle.Quant(bk, oracle.absmax_scale(dy_np, bk), seed, between)
+    qw = oracle.Quant(bk, oracle.absmax_scale(w_bits, bk), seed, wb + 2 * ab)
+    qa = oracle.Quant(bk, oracle.absmax_scale(a_np, bk), seed, wb + ab)
+    dar, daa = oracle.linear_bwd_data(dy_np, w_bits, qdy, qw, want_abs=True)
+    dwr, dwa = oracle.linear_bwd_weight(dy_np, a_np, qdy, qa, want_abs=True)
+    check_product(xa.grad.cpu().numpy(), dar, daa, "dA after an interleaved forward")
+    check_product(layer.dW.cpu().numpy(), dwr, dwa, "dW after an interleaved forward")
+    assert ref_end == 2 * wb + 2 * ab + (M * N + 7) // 8
+
+
+@pytest.mark.parametrize("kind", [L.INT8, L.E5M2, L.E4M2])
+def test_qat_objective_through_autograd(kind):
+    # Sec. 3.3 / Fig. 3: unquantized activation times Q(W) forward; the same Q(W), SR of the
+    # saved activation and of the output gradient backward
+    say("qat autograd linear", L.KIND_NAMES[kind])
+    M, K, N, seed = 80, 64, 48, 41
+    layer = train.SRLinear(K, N, seed, bwd_kind=kind, device=DEV, objective="qat")
+    g = torch.Generator(device=DEV).manual_seed(6)
+    x = torch.randn((M, K), device=DEV, generator=g).requires_grad_()
+    dy = torch.randn((M, N), device=DEV, generator=g) * 1e-3
+    y = layer(x)
+    y.backward(dy)
+    torch.cuda.synchronize()
+    a_np, w_bits, dy_np = x.detach().cpu().numpy(), host_src(layer.weight), dy.cpu().numpy()
+    wb, ab = (N * K + 7) // 8, (M * K + 7) // 8
+    qW = oracle.Quant(kind, oracle.absmax_scale(w_bits, kind), seed, 0)
+    qA = oracle.Quant(kind, oracle.absmax_scale(a_np, kind), seed, wb)
+    qdY = oracle.Quant(kind, oracle.absmax_scale(dy_np, kind), seed, wb + ab)
+    (yr, ya), (dar, daa), (dwr, dwa) = oracle.qat_pass(a_np, w_bits, dy_np, qW, qA, qdY, want_abs=True)
+    check_product(y.detach().cpu().numpy(), yr, ya, "Y")
+    check_product(x.grad.cpu().numpy(), dar, daa, "dA")
+    check_product(layer.dW.cpu().numpy(), dwr, dwa, "dW")
+    assert layer.position == wb + ab + (M * N + 7) // 8
+    # the weights of the two passes are one and the same set of codes
+    q = L.Quant(kind, float(np.float32(qW.scale)), seed=seed, counter_offset=0)
+    assert np.array_equal(L.sr_quantize(layer.weight, q).cpu().numpy(), qW(w_bits).reshape(-1))
+
+
+def test_qat_training_step_reduces_the_loss():
+    torch.manual_seed(0)
+    model = train.Decoder(vocab=512, d=64, heads=4, layers=2, seq=32, seed=3, device=DEV, objective="qat")
+    ids = torch.randint(0, 512, (8, 32), device=DEV)
+    tgt = torch.roll(ids, -1, dims=1)
+    losses = [float(train.train_step(model, ids, tgt, lr=0.05, micro_batches=2)) for _ in range(12)]
+    say("qat losses", [round(v, 3) for v in losses])
+    assert all(np.isfinite(losses)) and losses[-1] < losses[0] - 0.05
