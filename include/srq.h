@@ -61,7 +61,9 @@ typedef enum {
   SRQ_ERR_ALIGN = -4,       /* pointer or dimension not aligned as the entry point requires */
   SRQ_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than sr_linear_workspace_bytes     */
   SRQ_ERR_UNSUPPORTED = -6, /* valid but not implemented (e.g. int x float operand pair)    */
-  SRQ_ERR_HIP = -7          /* the HIP runtime reported an error at launch                  */
+  SRQ_ERR_HIP = -7,         /* the HIP runtime reported an error at launch                  */
+  SRQ_ERR_STATIC_LIMIT = -8 /* sr_linear_fwd_static: the call needs more scratch than the   */
+                            /* library's static array holds (SRQ_STATIC_SCRATCH_BYTES)      */
 } srq_status;
 
 typedef enum { SRQ_F32 = 0, SRQ_BF16 = 1 } srq_dtype; /* dtype of a source tensor */
@@ -199,6 +201,24 @@ size_t sr_gemm_e5m2_workspace_bytes(size_t P, size_t Q, size_t R);
 int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M,
                   size_t N, size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* sr_linear_fwd for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels, same results bit for bit as sr_linear_fwd; the scratch (quantized operands,
+ * slice partials) is a static device array of SRQ_STATIC_SCRATCH_BYTES inside the library, one
+ * copy per GPU, held until the process ends.  The call allocates nothing (no hipMalloc / hipFree,
+ * no allocating runtime or library routine); the array's address is looked up once per device on
+ * the first call there.  A call that would need a larger workspace than the array
+ * (sr_linear_workspace_bytes(SRQ_OP_FWD or SRQ_OP_FWD_WEIGHT_ONLY, M, N, K) > the limit) returns
+ * SRQ_ERR_STATIC_LIMIT and launches nothing; all other errors as sr_linear_fwd.
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents (nothing
+ * in it needs clearing: a call writes every byte it later reads).  Calls that overlap on one GPU
+ * -- different streams without ordering, or several host threads -- race on it: order them. */
+#define SRQ_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+size_t sr_linear_fwd_static_limit(void);
+int sr_linear_fwd_static(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M,
+                         size_t N, size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd,
+                         void* stream);
 
 /* Backward pass, Alg. 2, input gradient:  dA = Q(dY; qdY_bwd) Q(W; qW_bwd).
  * Weight-only objective: with qdY_bwd->kind == SRQ_NONE, dA = dY Q(W; qW_bwd), computed as in

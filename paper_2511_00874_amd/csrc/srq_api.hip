@@ -2,10 +2,17 @@
 // up Alg. 1 (forward) and Alg. 2 (backward).  Nothing here computes; every step of the path
 // runs in the kernels of srq_quantize.hip and srq_gemm.hip.
 #include <cmath>
+#include <mutex>
 
 #include "srq_internal.hpp"
 
 using namespace srq;
+
+// Device memory of the allocation-free entry point (sr_linear_fwd_static): the workspace that
+// sr_linear_fwd takes from its caller, as a file-scope array.  Every GPU the library runs on
+// holds its own copy at its own address until the process ends.  In host code this name is only
+// a handle for hipGetSymbolAddress; kernels and copies get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[SRQ_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -286,6 +293,23 @@ int run_weight_only(float* out, const void* x, int dtx, const void* w, int dtw, 
 
 bool is_none(const srq_quant* q) { return q && q->kind == SRQ_NONE; }
 
+// Address of `scratch` on the current device, looked up once per device (with that device
+// current) and kept.  Returns nullptr if the runtime refuses.
+constexpr int MAX_DEVICES = 64;
+void* static_scratch_ptr() {
+  static std::mutex lock;
+  static void* ptr[MAX_DEVICES] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> guard(lock);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    ptr[dev] = p;
+  }
+  return ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -470,6 +494,22 @@ int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW
                     workspace_bytes, stream);
 }
 
+// Alg. 1 for callers that may not allocate: the workspace is the library's static device array.
+size_t sr_linear_fwd_static_limit(void) { return SRQ_STATIC_SCRATCH_BYTES; }
+
+int sr_linear_fwd_static(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
+                         size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd, void* stream) {
+  // what sr_linear_fwd would ask of its caller for this call; beyond the array: refuse
+  const size_t need = sr_linear_workspace_bytes(is_none(qA_fwd) ? SRQ_OP_FWD_WEIGHT_ONLY : SRQ_OP_FWD, M, N, K);
+  if (need > SRQ_STATIC_SCRATCH_BYTES) return SRQ_ERR_STATIC_LIMIT;
+  void* ws = static_scratch_ptr();
+  if (!ws) return SRQ_ERR_HIP;
+  // every byte of the workspace that the product reads is written by this call's quantizer
+  // launch first (operand codes; slice partials by the product itself), so the array needs no
+  // clearing between calls
+  return sr_linear_fwd(Y, A, dtypeA, W, dtypeW, M, N, K, qA_fwd, qW_fwd, ws, SRQ_STATIC_SCRATCH_BYTES, stream);
+}
+
 // Alg. 2: dA = dYhat What.  Contraction over N: dY (M x N) as is, W (N x K) written as K x N.
 int sr_linear_bwd_data(float* dA, const void* dY, int dtypedY, const void* W, int dtypeW, size_t M,
                        size_t N, size_t K, const srq_quant* qdY_bwd, const srq_quant* qW_bwd,
@@ -644,6 +684,7 @@ const char* sr_status_string(int status) {
     case SRQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SRQ_ERR_UNSUPPORTED: return "unsupported combination";
     case SRQ_ERR_HIP: return "HIP launch error";
+    case SRQ_ERR_STATIC_LIMIT: return "problem needs more scratch than the static array of sr_linear_fwd_static holds";
     default: return "unknown status";
   }
 }

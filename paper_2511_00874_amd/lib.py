@@ -57,6 +57,9 @@ _lib.sr_gemm_e5m2_workspace_bytes.argtypes = [_sz, _sz, _sz]
 _lib.sr_gemm_e5m2_workspace_bytes.restype = _sz
 _lib.sr_linear_fwd.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _vp, _sz, _vp]
 _lib.sr_linear_bwd_data.argtypes = _lib.sr_linear_fwd.argtypes
+_lib.sr_linear_fwd_static.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _vp]
+_lib.sr_linear_fwd_static_limit.argtypes = []
+_lib.sr_linear_fwd_static_limit.restype = _sz
 _lib.sr_linear_bwd_weight.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp,
                                       C.c_float, _vp, _sz, _vp]
 _lib.sr_linear_bwd.argtypes = [_vp, _vp, _vp, C.c_int, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp,
@@ -70,14 +73,14 @@ _lib.sr_linear_bwd_stashed.argtypes = [_vp, _vp, _vp, C.c_int, _sz, _sz, _sz, _q
 _lib.sr_update_bf16.argtypes = [_vp, _vp, C.c_float, _sz, C.c_int, C.c_uint64, C.c_uint64, _vp]
 _lib.sr_status_string.argtypes = [C.c_int]
 _lib.sr_status_string.restype = C.c_char_p
-for _n in ("sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_gemm_e5m2", "sr_linear_fwd", "sr_linear_bwd_data",
+for _n in ("sr_linear_fwd_static", "sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_gemm_e5m2", "sr_linear_fwd", "sr_linear_bwd_data",
            "sr_linear_bwd_weight", "sr_linear_bwd", "sr_update_bf16", "sr_linear_fwd_stash", "sr_linear_bwd_stashed"):
     getattr(_lib, _n).restype = C.c_int
 
 EXPORTS = ["sr_absmax_scale", "sr_absmax_scales", "sr_absmax_workspace_bytes", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes", "sr_gemm_bf16", "sr_gemm_bf16_workspace_bytes", "sr_gemm_e5m2", "sr_gemm_e5m2_workspace_bytes",
            "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight", "sr_linear_bwd",
            "sr_linear_workspace_bytes", "sr_linear_stash_bytes", "sr_linear_fwd_stash", "sr_linear_bwd_stashed",
-           "sr_update_bf16", "sr_status_string"]
+           "sr_update_bf16", "sr_status_string", "sr_linear_fwd_static", "sr_linear_fwd_static_limit"]
 
 raw = _lib  # the C entry points themselves, for tests of the error paths
 
@@ -295,6 +298,16 @@ def sr_linear_fwd(A, W, qA, qW, out=None, workspace=None):
     ws = _ws(OP_FWD_WEIGHT_ONLY if qA.kind == NONE else OP_FWD, M, N, K, workspace, A.device)
     _check(_lib.sr_linear_fwd(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K,
                               C.byref(qA.c()), C.byref(qW.c()), _dev(ws), ws.numel(), _stream()))
+    return out
+
+
+def sr_linear_fwd_static(A, W, qA, qW, out):
+    """sr_linear_fwd with the library's static scratch array as workspace; `out` is required (this
+    call is for callers that may not allocate)."""
+    M, K = A.shape
+    N = W.shape[0]
+    _check(_lib.sr_linear_fwd_static(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K,
+                                     C.byref(qA.c()), C.byref(qW.c()), _stream()))
     return out
 
 

@@ -42,8 +42,8 @@ def test_struct_layout_matches_header(lib):
 
 
 def test_status_strings(lib):
-    seen = {lib.status_string(s) for s in range(0, -8, -1)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {lib.status_string(s) for s in range(0, -9, -1)}
+    assert len(seen) == 9 and "ok" in seen
     assert lib.status_string(-99) == "unknown status"
 
 
