@@ -1,12 +1,15 @@
 """Benchmark of the SR-quantized linear hot path on one MI355X.
 
-One step = one pass of the whole hot path over one batch of synthetic input: for each of the
-two GPT-2-small MLP linears (d=768, d_ff=3072) at 8192 tokens, the five per-tensor absmax
-scales, the five SR quantizations (int8 forward, E5M2 backward) and the three products
+Headline workload: the seven linears of one Llama-1B-shaped decoder layer (q, k, v, o:
+2048 x 2048; gate, up: 5632 x 2048; down: 2048 x 5632) at 65536 tokens, master weights in
+bfloat16, the output gradient on the 4-bit integer grid and the other four quantizers on the
+8-bit one.  One step = one pass of the whole hot path over that batch: per linear the five
+per-tensor absmax scales, the five SR quantizations and the three products
 Y = Q(A)Q(W)^T, dA = Q(dY)Q(W), dW = Q(dY)^T Q(A).  Inputs are resident in HBM before the
-timed region.  Prints ONE JSON line; extra keys carry the standalone-quantizer sweep
-(2^28 fp32 elements -> int8 / int4 / E4M3 / E5M2), the kernel rooflines and the CPU oracle
-timed on the host cores.
+timed region.  Prints ONE JSON line; extra keys carry the token sweep (4096 / 16384 tokens),
+the GPT-2-small MLP workload (int8 forward, E5M2 backward; also replayed from a HIP graph),
+the standalone-quantizer sweep (2^28 fp32 elements -> int8 / int4 / E4M3 / E5M2), whole
+training steps of the small decoder, the kernel rooflines and the CPU oracle timed on the host.
 """
 import argparse
 import json
@@ -19,33 +22,25 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by what the same counters
-# read for a plain copy of known size (profiles/bench_hbm_traffic.txt): mean over the three
-# launches per step of the bf16 128 x 128 product kernel, and the int8 quantizer on 2^28 elements
-# mean over the three launches of that kernel in a step: fc2's input gradient (8192 x 3072 out,
-# contraction 768) and the two weight gradients (2.36 M outputs, contraction 8192), one-byte operands
-ALGORITHMIC_F16_PRODUCT_128 = ((8192 * 768 + 3072 * 768 + 4 * 8192 * 3072) + 2 * (3072 * 8192 + 768 * 8192 + 4 * 3072 * 768)) / 3
-# measured HBM bytes of the same three launches, slice sums included (rocprofv3 FETCH_SIZE / WRITE_SIZE)
-TRAFFIC_F16_PRODUCT_128 = (2 * (52.7 + 27.0 + 27.0 + 9.0) + (24.2 + 96.2)) / 3 * 2**20
-TRAFFIC_QUANTIZE_INT8_2P28 = (1024.0 + 256.0) * 2**20
 MFMA_PEAK_TFLOPS = {"int8": 5000.0, "fp8": 5000.0, "bf16": 2500.0, "fp16": 2500.0}
-TOKENS = 8192
-FWD_KIND, BWD_KIND = "int8", "e5m2"
+TOKENS = 65536
+GPT2_TOKENS = 8192
+# HBM bytes per launch of the dominant kernel (int8 product, 256 x 256 tiles) on the nine products of
+# the headline workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by what the same counters
+# read for a plain copy of known size (profiles/llama_hbm_traffic.txt); None until measured
+TRAFFIC_I8_PRODUCT_LLAMA = None
+TRAFFIC_QUANTIZE_INT8_2P28 = (1024.0 + 256.0) * 2**20
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-quantizer-sweep", action="store_true")
-    ap.add_argument("--train-step", action="store_true",
-                    help="also time whole training steps of the small decoder at batch 8, 32 and 128")
-    ap.add_argument("--llama-sweep", action="store_true",
-                    help="also time the Llama-1B-shaped linears (bf16 weights, 4-bit output gradient, 8-bit "
-                         "elsewhere) at 4096, 16384 and 65536 tokens, with the error of dW for a 4-bit against "
-                         "an 8-bit output gradient")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="headline step and its roofline only (for profiling runs)")
+    ap.add_argument("--only", default="", help="run only this extra section (profiling runs): gpt2, products")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB device copy (known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -55,7 +50,7 @@ def parse():
 class Layer:
     """One linear's tensors, scales, quantizers, outputs and workspaces, all preallocated."""
 
-    def __init__(self, L, synth, torch, name, M, N, K, seed, f8_flag, kinds=None, w_bf16=False):
+    def __init__(self, L, synth, torch, name, M, N, K, seed, f8_flag=0, kinds=None, w_bf16=False, counters_dev=False):
         dev = "cuda:0"
         self.name, self.M, self.N, self.K = name, M, N, K
         self.A = synth.gaussian_torch((M, K), 1.0, seed, dev)
@@ -67,13 +62,21 @@ class Layer:
         src = {"A": self.A, "W": self.W, "dY": self.dY}
         self.scales = torch.empty(5, dtype=torch.float32, device=dev)
         self.q, self.src_of = {}, {}
+        offs = []
         off = 0
+        for qn in kinds:
+            offs.append(off)
+            off += (src[qn.split("_")[0]].numel() + 7) // 8
+        # stream positions on the device: a captured step is replayed with fresh thresholds by
+        # advancing these words (one add kernel per step)
+        self.counters = torch.tensor(offs, dtype=torch.int64, device=dev) if counters_dev else None
+        self.advance = off
         for i, (qn, kind) in enumerate(kinds.items()):
             t = src[qn.split("_")[0]]
-            self.q[qn] = L.Quant(kind, self.scales[i:i + 1], seed=seed, counter_offset=off,
+            self.q[qn] = L.Quant(kind, self.scales[i:i + 1], seed=seed,
+                                 counter_offset=self.counters[i:i + 1] if counters_dev else offs[i],
                                  flags=f8_flag if kind in (L.E4M3, L.E5M2) else 0)
             self.src_of[qn] = (t, kind, self.scales[i:i + 1])
-            off += (t.numel() + 7) // 8
         self.Y = torch.empty((M, N), dtype=torch.float32, device=dev)
         self.dA = torch.empty((M, K), dtype=torch.float32, device=dev)
         self.dW = torch.empty((N, K), dtype=torch.float32, device=dev)
@@ -83,13 +86,12 @@ class Layer:
 
     def step(self, L):
         # a0: five scales (three passes: A and W feed two formats each); a1-a5: forward, then the
-        # backward pass with one Q(dY) for both products.  (The variant that saves the backward
-        # codes of A and W during the forward pass, sr_linear_fwd_stash, moves fewer bytes but is
-        # no faster here: its forward quantizer does two quantizations per element loaded and its
-        # products read operands that have left the last-level cache.  It is there to save memory.)
+        # backward pass with one Q(dY) for both products
         self.absmax.run()
         self.forward(L)
         self.backward(L)
+        if self.counters is not None:
+            self.counters.add_(self.advance)
 
     def forward(self, L):
         L.sr_linear_fwd(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], out=self.Y, workspace=self.ws)
@@ -100,6 +102,11 @@ class Layer:
 
     def flops(self):
         return 6.0 * self.M * self.N * self.K
+
+    def min_hbm_bytes(self):
+        """Every fp32 / bf16 tensor in once per quantizer pass, every result out once."""
+        ew = self.W.element_size()
+        return 4.0 * 3 * self.M * self.K + ew * 3.0 * self.N * self.K + 4.0 * 2 * self.M * self.N
 
 
 def time_steps(torch, fn, steps, warmup):
@@ -136,6 +143,198 @@ def event_ms(torch, fn, reps, warmup=3, warm_ms=30.0):
     return a.elapsed_time(b) / reps
 
 
+LLAMA_KINDS = ("A_fwd", "W_fwd", "A_bwd", "W_bwd")
+
+
+def llama_layers(L, synth, torch, T, shapes, seed0=7):
+    kinds = {k: L.INT8 for k in LLAMA_KINDS}
+    kinds["dY_bwd"] = L.INT4
+    return [Layer(L, synth, torch, nm, T, N, K, seed0 + 10 * i, kinds=kinds, w_bf16=True)
+            for i, (nm, N, K) in enumerate(shapes)]
+
+
+def llama_products_roofline(L, torch, reps):
+    """The dominant kernel of the headline step alone: the int8 product kernel on the nine products
+    of the three distinct layer shapes at 65536 tokens (operands already quantized), timed by HIP
+    events on the stream it is launched on."""
+    dev = "cuda:0"
+    T = TOKENS
+    shapes = []
+    for N, K in ((2048, 2048), (5632, 2048), (2048, 5632)):
+        shapes += [(T, N, K), (T, K, N), (N, K, T)]  # Y, dA, dW as out (P x Q), contraction R
+    calls, flops, alg_bytes = [], 0.0, 0.0
+    for (P, Q, R) in shapes:
+        need = L.raw.sr_gemm_workspace_bytes(P, Q, R)
+        X = torch.randint(-127, 128, (P, R), dtype=torch.int8, device=dev).view(torch.uint8)
+        Z = torch.randint(-127, 128, (Q, R), dtype=torch.int8, device=dev).view(torch.uint8)
+        calls.append((X, Z, torch.empty((P, Q), dtype=torch.float32, device=dev),
+                      torch.empty(max(need, 16), dtype=torch.uint8, device=dev)))
+        flops += 2.0 * P * Q * R
+        alg_bytes += P * R + Q * R + 4.0 * P * Q
+
+    def run():
+        for X, Z, o, ws in calls:
+            L.sr_gemm_codes(X, L.INT8, Z, L.INT8, out=o, workspace=ws)
+    ms = event_ms(torch, run, reps) / len(calls)
+    fl = flops / len(calls)
+    tf = fl / (ms * 1e-3) / 1e12
+    del calls
+    torch.cuda.empty_cache()
+    return {"bound": "mfma", "kernel": "gemm_nt_kernel<I8Mma, 256, 256, ...> (int8 codes, int32 accumulators)",
+            "achieved": round(tf, 1), "peak": MFMA_PEAK_TFLOPS["int8"], "unit": "TFLOP/s",
+            "frac": round(tf / MFMA_PEAK_TFLOPS["int8"], 4), "traffic": TRAFFIC_I8_PRODUCT_LLAMA,
+            "launches": len(shapes), "avg_launch_us": round(ms * 1e3, 2), "flop_per_launch": fl,
+            "algorithmic_bytes_per_launch": alg_bytes / len(shapes),
+            "note": "mean over the nine products (Y, dA, dW of the 2048x2048, 5632x2048 and 2048x5632 layers at "
+                    "65536 tokens), operands already quantized; algorithmic bytes = both operands once + the "
+                    "fp32 result once; the weight-gradient launches include the sum of their contraction slices"}
+
+
+def token_sweep(L, synth, torch):
+    """The same linears at 4096 and 16384 tokens (whole layer step by HIP events) and, per token
+    count incl. 65536, the batch-for-bits figure of Sec. 4.2 on the 2048 x 2048 layer: rms error of
+    the mean gradient dW / T against the product of the unquantized tensors (binary64 on the device,
+    256 rows of dW) with a 4-bit and with an 8-bit output gradient: it falls like 1 / sqrt(T) and
+    scales with the step of the format."""
+    out = {}
+    shapes = (("qkvo", 2048, 2048), ("gate_up", 5632, 2048), ("down", 2048, 5632))
+    for T in (4096, 16384, 65536):
+        row = {}
+        for name, N, K in shapes:
+            if T == TOKENS and name != "qkvo":
+                continue  # timed by the headline step
+            ly = llama_layers(L, synth, torch, T, [(name, N, K)])[0]
+            ms = event_ms(torch, lambda: ly.step(L), 10)
+            row[name] = {"us": round(ms * 1e3, 1), "TFLOP/s": round(ly.flops() / ms / 1e9, 1)}
+            if name == "qkvo":
+                exact = ly.dY[:, :256].double().t() @ ly.A.double()
+                err = {"int4": float((ly.dW[:256].double() - exact).pow(2).mean().sqrt()) / T}
+                kinds8 = {k: L.INT8 for k in LLAMA_KINDS + ("dY_bwd",)}
+                l8 = Layer(L, synth, torch, name, T, N, K, 7, kinds=kinds8, w_bf16=True)
+                l8.step(L)
+                err["int8"] = float((l8.dW[:256].double() - exact).pow(2).mean().sqrt()) / T
+                row["rms_error_of_dW_over_T"] = {k: float("%.3g" % v) for k, v in err.items()}
+                del l8, exact
+            del ly
+            torch.cuda.empty_cache()
+        out["T%d" % T] = row
+    return out
+
+
+def gpt2_mlp(L, synth, torch, steps, warmup):
+    """The GPT-2-small MLP linears (fc1 3072 x 768, fc2 768 x 3072) at 8192 tokens, int8 forward and
+    E5M2 backward quantizers: step time from direct launches, the same step replayed from a HIP
+    graph (stream positions on the device, advanced inside the graph), the entry-point split, and
+    the product kernels alone."""
+    shapes = synth.GPT2_SMALL_MLP
+    res = {"workload": "fc1 (3072x768) + fc2 (768x3072), 8192 tokens, fp32 in/out, int8 SR forward, E5M2 SR backward"}
+    flops = 2 * 6.0 * GPT2_TOKENS * 768 * 3072
+    io_bytes = sum(4.0 * (3 * GPT2_TOKENS * K + 3 * N * K + 2 * GPT2_TOKENS * N) for _, N, K in shapes)
+    res["flop_per_step"], res["min_hbm_bytes_per_step"] = flops, io_bytes
+    res["composite_ceiling_TFLOP/s"] = round(flops / (io_bytes / (HBM_PEAK_GBS * 1e9)) / 1e12, 1)
+    for label, flag in (("exact", 0), ("f8_pipeline", L.FLAG_F8_PIPELINE)):
+        layers = [Layer(L, synth, torch, nm, GPT2_TOKENS, N, K, 100 + 10 * i, flag) for i, (nm, N, K) in enumerate(shapes)]
+
+        def step():
+            for ly in layers:
+                ly.step(L)
+        sec = time_steps(torch, step, steps, warmup)
+        res[label] = {"ms_per_step": round(sec * 1e3, 4), "TFLOP/s": round(flops / sec / 1e12, 1)}
+        if label == "exact":
+            def step_given_scales():
+                for ly in layers:
+                    ly.forward(L)
+                    ly.backward(L)
+            sec_gs = time_steps(torch, step_given_scales, steps, warmup)
+            res["scales_given"] = {"ms_per_step": round(sec_gs * 1e3, 4), "TFLOP/s": round(flops / sec_gs / 1e12, 1)}
+            # the same step recorded once and replayed: one graph launch per step instead of 14
+            glayers = [Layer(L, synth, torch, nm, GPT2_TOKENS, N, K, 100 + 10 * i, flag, counters_dev=True)
+                       for i, (nm, N, K) in enumerate(shapes)]
+
+            def gstep():
+                for ly in glayers:
+                    ly.step(L)
+            g = torch.cuda.CUDAGraph()
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                gstep()
+                torch.cuda.synchronize()
+                g.capture_begin()
+                gstep()
+                g.capture_end()
+            torch.cuda.synchronize()
+            sec_g = time_steps(torch, g.replay, steps, warmup)
+            res["graph"] = {"ms_per_step": round(sec_g * 1e3, 4), "TFLOP/s": round(flops / sec_g / 1e12, 1),
+                            "note": "HIP graph of the whole step; stream positions live on the device and are "
+                                    "advanced inside the graph, so every replay draws fresh thresholds"}
+            del g, glayers
+            res["phases"] = phase_times(L, torch, layers, max(5, steps // 2))
+            res["product_kernels"] = gpt2_product_kernels(L, torch, layers, max(5, steps // 2))
+        del layers
+        torch.cuda.empty_cache()
+    return res
+
+
+def gpt2_product_kernels(L, torch, layers, reps):
+    """The product kernels alone on the GPT-2 shapes, operands already quantized: the f16 pipeline
+    fed from E5M2 codes (backward products), the int8 pipeline (forward products), the fp8
+    pipeline (backward products with the flag set)."""
+    dev = "cuda:0"
+    out = {}
+
+    def codes(P, R):
+        return torch.randint(0, 120, (P, R), dtype=torch.uint8, device=dev)
+
+    fwd_shapes = [(ly.M, ly.N, ly.K) for ly in layers]
+    bwd_shapes = [s for ly in layers for s in ((ly.M, ly.K, ly.N), (ly.N, ly.K, ly.M))]
+    for name, shapes, call, need_fn, peak in (
+            ("f16", bwd_shapes, lambda X, Z, o, ws: L.sr_gemm_e5m2(X, Z, out=o, workspace=ws),
+             L.raw.sr_gemm_e5m2_workspace_bytes, MFMA_PEAK_TFLOPS["fp16"]),
+            ("int8", fwd_shapes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.INT8, Z, L.INT8, out=o, workspace=ws),
+             L.raw.sr_gemm_workspace_bytes, MFMA_PEAK_TFLOPS["int8"]),
+            ("fp8", bwd_shapes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.E5M2, Z, L.E5M2, out=o, workspace=ws),
+             L.raw.sr_gemm_workspace_bytes, MFMA_PEAK_TFLOPS["fp8"])):
+        calls, flops = [], 0.0
+        for (P, Q, R) in shapes:
+            need = need_fn(P, Q, R)
+            calls.append((codes(P, R), codes(Q, R), torch.empty((P, Q), dtype=torch.float32, device=dev),
+                          torch.empty(max(need, 16), dtype=torch.uint8, device=dev)))
+            flops += 2.0 * P * Q * R
+
+        def run():
+            for X, Z, o, ws in calls:
+                call(X, Z, o, ws)
+        ms = event_ms(torch, run, reps) / len(calls)
+        fl = flops / len(calls)
+        tf = fl / (ms * 1e-3) / 1e12
+        out[name] = {"launches": len(calls), "avg_launch_us": round(ms * 1e3, 2), "flop_per_launch": fl,
+                     "TFLOP/s": round(tf, 1), "peak": peak, "frac": round(tf / peak, 4)}
+        del calls
+    torch.cuda.empty_cache()
+    return out
+
+
+def phase_times(L, torch, layers, reps):
+    """Entry-point level split of one step, by HIP events."""
+    def absmax():
+        for ly in layers:
+            ly.absmax.run()
+
+    def fwd():
+        for ly in layers:
+            ly.forward(L)
+
+    def bwd():
+        for ly in layers:
+            ly.backward(L)
+    res = {n: round(event_ms(torch, f, reps) * 1e3, 1) for n, f in (("absmax_us", absmax), ("fwd_us", fwd), ("bwd_us", bwd))}
+    nbytes = sum(ly.A.numel() * ly.A.element_size() + ly.W.numel() * ly.W.element_size() + 4 * ly.dY.numel()
+                 for ly in layers)
+    res["absmax_GB/s"] = round(nbytes / (res["absmax_us"] * 1e-6) / 1e9, 1)
+    return res
+
+
 def quantizer_sweep(L, synth, torch, reps):
     """Standalone SR quantize of 2^28 fp32 values ~N(0,1) with 1% outliers ~N(0,50)."""
     n = 1 << 28
@@ -164,157 +363,78 @@ def quantizer_sweep(L, synth, torch, reps):
     return res
 
 
-def train_step_times(torch, steps=3):
+def train_step_times(torch, steps=2):
     """Whole training step of the 12-layer decoder (d = 768, 12 heads, vocabulary 32000, 1024
     tokens per sequence, random weights and token ids): forward, backward and the updates, every
-    linear through the SR-quantized path, weights in bfloat16 updated by Eq. 10.  Also the
-    weight-only objective of Sec. 3.2 (int8 weights, binary32 activations and gradients) at the
-    smallest batch."""
+    linear through the SR-quantized path (int8 forward, E5M2 backward quantizers), weights in
+    bfloat16 updated by Eq. 10; batch 8, 32 and 128 (the last as 4 micro-batches of 32)."""
     from paper_2511_00874_amd import train
-    out = {}
-    for label, weight_only, batches in (("five_quantizers", False, ((8, 1), (32, 1), (128, 4))),
-                                        ("weight_only", True, ((8, 1),))):
-        model = train.Decoder(weight_only=weight_only)
-        out["model"] = ("decoder 12 x 768, 12 heads, vocab 32000, seq 1024; %.1f M weights in SR linears"
-                        % (sum(m.in_features * m.out_features for m in model.sr_linears()) / 1e6))
-        res = {}
-        for b, micro in batches:
-            ids = torch.randint(0, 32000, (b, 1024), device="cuda:0")
-            tgt = torch.roll(ids, -1, 1)
-            train.train_step(model, ids, tgt, 1e-3, micro)
-            sec = time_steps(torch, lambda: train.train_step(model, ids, tgt, 1e-3, micro), steps, 0)
-            res["b%d" % b] = {"ms_per_step": round(sec * 1e3, 2), "micro_batches": micro,
-                              "sr_linear_TFLOP/s": round(train.flops_per_token(model) * b * 1024 / sec / 1e12, 1)}
-        out[label] = res
-        del model
-        torch.cuda.empty_cache()
-    return out
-
-
-def llama_sweep(L, synth, torch):
-    """Config 4: the Llama-1B-shaped linears, weights held in bfloat16, the output gradient on the
-    4-bit integer grid and the other four quantizers on the 8-bit one, whole layer step (scales,
-    quantizers, three products) by HIP events.  Per token count also the batch-for-bits figure of
-    Sec. 4.2 on the 2048 x 2048 layer: rms error of the mean gradient dW / T against the product
-    of the unquantized tensors (binary64 on the device, 256 rows of dW), with a 4-bit and with an
-    8-bit output gradient: it falls like 1 / sqrt(T) and scales with the step of the format."""
-    out = {}
-    i8 = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.INT8, "W_bwd": L.INT8}
-    for T in (4096, 16384, 65536):
-        row = {}
-        for name, N, K in (("qkvo", 2048, 2048), ("gate_up", 5632, 2048), ("down", 2048, 5632)):
-            ly = Layer(L, synth, torch, name, T, N, K, 7, 0, kinds=dict(i8, dY_bwd=L.INT4), w_bf16=True)
-            ms = event_ms(torch, lambda: ly.step(L), 10)
-            row[name] = {"us": round(ms * 1e3, 1), "TFLOP/s": round(ly.flops() / ms / 1e9, 1)}
-            if name == "qkvo":
-                exact = ly.dY[:, :256].double().t() @ ly.A.double()
-                ref = float(T)
-                err = {"int4": float((ly.dW[:256].double() - exact).pow(2).mean().sqrt()) / ref}
-                l8 = Layer(L, synth, torch, name, T, N, K, 7, 0, kinds=dict(i8, dY_bwd=L.INT8), w_bf16=True)
-                l8.step(L)
-                err["int8"] = float((l8.dW[:256].double() - exact).pow(2).mean().sqrt()) / ref
-                row["rms_error_of_dW_over_T"] = {k: float("%.3g" % v) for k, v in err.items()}
-                del l8, exact
-            del ly
-            torch.cuda.empty_cache()
-        out["T%d" % T] = row
-    return out
-
-
-def product_kernel_rooflines(L, torch, layers, reps):
-    """The product kernels alone, operands already quantized, timed by HIP events on the stream
-    they are launched on: the f16 pipeline fed from E5M2 codes (backward products of the default
-    path), the int8 pipeline (forward products) and the fp8 pipeline (backward products with the
-    flag set), each over the same shapes the step launches them on."""
-    dev = "cuda:0"
-    out = {}
-
-    def codes(P, R):
-        return torch.randint(0, 120, (P, R), dtype=torch.uint8, device=dev)
-
-    fwd_shapes = [(ly.M, ly.N, ly.K) for ly in layers]
-    bwd_shapes = [s for ly in layers for s in ((ly.M, ly.K, ly.N), (ly.N, ly.K, ly.M))]
-    # the backward products that run the 128 x 128-tile instantiation (the 8192 x 768 output of
-    # fc1's input gradient takes the 128 x 192 one): fc2's input gradient and both weight gradients
-    bwd128 = [s for s in bwd_shapes if not (s[0] == TOKENS and s[1] == 768)]
-    for name, shapes, make, call, need_fn, peak, kernel in (
-            ("f16", bwd128, codes, lambda X, Z, o, ws: L.sr_gemm_e5m2(X, Z, out=o, workspace=ws),
-             L.raw.sr_gemm_e5m2_workspace_bytes, MFMA_PEAK_TFLOPS["fp16"], "gemm_nt_kernel<E5M2F16Mma, 128, 128, 2, 2, 2>"),
-            ("int8", fwd_shapes, codes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.INT8, Z, L.INT8, out=o, workspace=ws),
-             L.raw.sr_gemm_workspace_bytes, MFMA_PEAK_TFLOPS["int8"], "gemm_nt_kernel<I8Mma, 128, ...>"),
-            ("fp8", bwd_shapes, codes, lambda X, Z, o, ws: L.sr_gemm_codes(X, L.E5M2, Z, L.E5M2, out=o, workspace=ws),
-             L.raw.sr_gemm_workspace_bytes, MFMA_PEAK_TFLOPS["fp8"], "gemm_nt_kernel<F8Mma<1,1>, 128, ...>")):
-        calls, flops = [], 0.0
-        for (P, Q, R) in shapes:
-            need = need_fn(P, Q, R)
-            calls.append((make(P, R), make(Q, R), torch.empty((P, Q), dtype=torch.float32, device=dev),
-                          torch.empty(max(need, 16), dtype=torch.uint8, device=dev)))
-            flops += 2.0 * P * Q * R
-
-        def run():
-            for X, Z, o, ws in calls:
-                call(X, Z, o, ws)
-        ms = event_ms(torch, run, reps) / len(calls)
-        fl = flops / len(calls)
-        tf = fl / (ms * 1e-3) / 1e12
-        out[name] = {"kernel": kernel, "launches": len(calls), "avg_launch_us": round(ms * 1e3, 2),
-                     "flop_per_launch": fl, "TFLOP/s": round(tf, 1), "peak": peak, "frac": round(tf / peak, 4)}
-        del calls
+    model = train.Decoder()
+    out = {"model": "decoder 12 x 768, 12 heads, vocab 32000, seq 1024; %.1f M weights in SR linears"
+                    % (sum(m.in_features * m.out_features for m in model.sr_linears()) / 1e6)}
+    for b, micro in ((8, 1), (32, 1), (128, 4)):
+        ids = torch.randint(0, 32000, (b, 1024), device="cuda:0")
+        tgt = torch.roll(ids, -1, 1)
+        train.train_step(model, ids, tgt, 1e-3, micro)
+        sec = time_steps(torch, lambda: train.train_step(model, ids, tgt, 1e-3, micro), steps, 0)
+        out["b%d" % b] = {"ms_per_step": round(sec * 1e3, 2), "micro_batches": micro,
+                          "sr_linear_TFLOP/s": round(train.flops_per_token(model) * b * 1024 / sec / 1e12, 1)}
+    del model
     torch.cuda.empty_cache()
     return out
 
 
-def phase_times(L, torch, layers, reps):
-    """Entry-point level split of one step, by HIP events."""
-    def absmax():
-        for ly in layers:
-            ly.absmax.run()
-
-    def fwd():
-        for ly in layers:
-            ly.forward(L)
-
-    def bwd():
-        for ly in layers:
-            ly.backward(L)
-    res = {n: round(event_ms(torch, f, reps) * 1e3, 1) for n, f in (("absmax_us", absmax), ("fwd_us", fwd), ("bwd_us", bwd))}
-    nbytes = sum(4 * (ly.A.numel() + ly.W.numel() + ly.dY.numel()) for ly in layers)
-    res["absmax_GB/s"] = round(nbytes / (res["absmax_us"] * 1e-6) / 1e9, 1)
-    return res
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
-def cpu_baseline(layers_shape):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: the five absmax
-    scales and five quantizations of fc1 in full (8192 tokens) and the three products on 2^20
-    sampled output entries each."""
+def cpu_baseline():
+    """The CPU oracle, as it stands, on a bounded sample of the headline workload: the 2048 x 2048
+    linear with bfloat16 weights, 8-bit quantizers and a 4-bit output gradient; per run the five
+    absmax scales, the quantizations Alg. 1 / Alg. 2 state (each product quantizes its two
+    operands) of the full tensors at `T` tokens, then `n_out` sampled entries of each of Y, dA, dW.
+    Once on all host threads and once, on a smaller sample, on a single thread."""
     import numpy as np
 
     import oracle
     from paper_2511_00874_amd import synth
-    name, N, K = layers_shape[0]
-    M = TOKENS
-    A, W, dY = synth.single_layer(M, N, K, seed=0, std_dy=1e-3)
-    t0 = time.perf_counter()
-    q = {}
-    off = 0
-    for qn, x, kind in (("A_fwd", A, oracle.INT8), ("W_fwd", W, oracle.INT8), ("A_bwd", A, oracle.E5M2),
-                        ("W_bwd", W, oracle.E5M2), ("dY_bwd", dY, oracle.E5M2)):
-        q[qn] = oracle.Quant(kind, oracle.absmax_scale(x, kind), 0, off)
-        off += (x.size + 7) // 8
-    rng = np.random.default_rng(0)
-    n_out = 1 << 20
-    flops = 0.0
-    oracle.linear_fwd(A, W, q["A_fwd"], q["W_fwd"], at=rng.integers(0, M * N, n_out).astype(np.uint64))
-    flops += 2.0 * n_out * K
-    oracle.linear_bwd_data(dY, W, q["dY_bwd"], q["W_bwd"], at=rng.integers(0, M * K, n_out).astype(np.uint64))
-    flops += 2.0 * n_out * N
-    oracle.linear_bwd_weight(dY, A, q["dY_bwd"], q["A_bwd"], at=rng.integers(0, N * K, n_out).astype(np.uint64))
-    flops += 2.0 * n_out * M
-    dt = time.perf_counter() - t0
-    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"fc1 at {M} tokens: 5 absmax + 5 quantizations of the full tensors (each product re-quantizes "
-                      f"its operands, as Alg. 1/2 state), then 3 x {n_out} sampled entries of Y/dA/dW; "
-                      f"{flops / 1e9:.1f} GFLOP of products in {dt:.1f} s wall"}
+    N = K = 2048
+
+    def run(T, n_out):
+        A, W, dY = synth.single_layer(T, N, K, seed=0, std_dy=1e-3)
+        Wb = synth.to_bf16_bits(W)
+        t0 = time.perf_counter()
+        q, off = {}, 0
+        for qn, x, kind in (("A_fwd", A, oracle.INT8), ("W_fwd", Wb, oracle.INT8), ("A_bwd", A, oracle.INT8),
+                            ("W_bwd", Wb, oracle.INT8), ("dY_bwd", dY, oracle.INT4)):
+            q[qn] = oracle.Quant(kind, oracle.absmax_scale(x, kind), 0, off)
+            off += (x.size + 7) // 8
+        rng = np.random.default_rng(0)
+        oracle.linear_fwd(A, Wb, q["A_fwd"], q["W_fwd"], at=rng.integers(0, T * N, n_out).astype(np.uint64))
+        oracle.linear_bwd_data(dY, Wb, q["dY_bwd"], q["W_bwd"], at=rng.integers(0, T * K, n_out).astype(np.uint64))
+        oracle.linear_bwd_weight(dY, A, q["dY_bwd"], q["A_bwd"], at=rng.integers(0, N * K, n_out).astype(np.uint64))
+        dt = time.perf_counter() - t0
+        flops = 2.0 * n_out * (K + N + T)
+        return flops / dt / 1e12, dt, flops
+
+    threads = oracle.threads()
+    v_all, dt_all, fl_all = run(4096, 1 << 19)
+    oracle.set_threads(1)
+    v_one, dt_one, fl_one = run(512, 1 << 17)
+    oracle.set_threads(threads)
+    return {"value": round(v_all, 6), "unit": "TFLOP/s", "cores": threads, "kind": "oracle", "cpu_model": cpu_model(),
+            "sample": f"2048x2048 linear (bf16 W, int8 quantizers, int4 dY) at 4096 tokens: 5 absmax + the 6 "
+                      f"quantizations of the full tensors, then 3 x {1 << 19} sampled entries of Y/dA/dW; "
+                      f"{fl_all / 1e9:.1f} GFLOP of products in {dt_all:.1f} s wall",
+            "single_thread": {"value": round(v_one, 6), "unit": "TFLOP/s", "cores": 1,
+                              "sample": f"the same at 512 tokens with 3 x {1 << 17} sampled entries; "
+                                        f"{fl_one / 1e9:.1f} GFLOP of products in {dt_one:.1f} s wall"}}
 
 
 def main():
@@ -331,33 +451,30 @@ def main():
         print("bench.py needs a GPU (there is no CPU path)", file=sys.stderr)
         sys.exit(2)
 
-    shapes = synth.GPT2_SMALL_MLP
-    result, phases, rl = {}, None, None
-    for label, flag in (("exact", 0), ("f8_pipeline", L.FLAG_F8_PIPELINE)):
-        layers = [Layer(L, synth, torch, nm, TOKENS, N, K, 100 + 10 * i, flag) for i, (nm, N, K) in enumerate(shapes)]
+    if args.only == "gpt2":
+        print(json.dumps({"gpt2_mlp": gpt2_mlp(L, synth, torch, args.steps, args.warmup)}))
+        return
+    if args.only == "products":
+        print(json.dumps({"roofline": llama_products_roofline(L, torch, max(5, args.steps // 2))}))
+        return
 
-        def step():
-            for ly in layers:
-                ly.step(L)
-        sec = time_steps(torch, step, args.steps, args.warmup)
-        flops = sum(ly.flops() for ly in layers)
-        result[label] = (sec, flops / sec / 1e12)
-        if label == "exact":
-            # the same steps with the scales taken as given (they are inputs of the entry points)
-            def step_given_scales():
-                for ly in layers:
-                    ly.forward(L)
-                    ly.backward(L)
-            sec_gs = time_steps(torch, step_given_scales, args.steps, args.warmup)
-            result["given_scales"] = (sec_gs, flops / sec_gs / 1e12)
-            reps = max(5, args.steps // 2)
-            phases = phase_times(L, torch, layers, reps)
-            rl = product_kernel_rooflines(L, torch, layers, reps)
-        del layers
-        torch.cuda.empty_cache()
+    layers = llama_layers(L, synth, torch, TOKENS, synth.LLAMA_1B_LINEARS)
 
-    sec, tflops = result["exact"]
-    io_bytes = sum(4.0 * (3 * TOKENS * K + 3 * N * K + 2 * TOKENS * N) for _, N, K in shapes)
+    def step():
+        for ly in layers:
+            ly.step(L)
+    sec = time_steps(torch, step, args.steps, args.warmup)
+    flops = sum(ly.flops() for ly in layers)
+    io_bytes = sum(ly.min_hbm_bytes() for ly in layers)
+    tflops = flops / sec / 1e12
+    per_shape = {}
+    for name, idx in (("qkvo_2048x2048", 0), ("gate_up_5632x2048", 4), ("down_2048x5632", 6)):
+        ms = event_ms(torch, lambda: layers[idx].step(L), 5)
+        per_shape[name] = {"us": round(ms * 1e3, 1), "TFLOP/s": round(layers[idx].flops() / ms / 1e9, 1)}
+    phases = phase_times(L, torch, layers, 5)
+    del layers
+    torch.cuda.empty_cache()
+
     line = {
         "metric": "SR-quantized linear fwd+bwd TFLOP/s",
         "value": round(tflops, 2),
@@ -369,46 +486,31 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int8 (i32 acc) forward; e5m2 codes widened to f16 on the f16 pipeline (f32 acc) backward",
+        "dtype": "int8 (int4 values for dY), int32 accumulators",
         "data": "synthetic",
-        "config": {"workload": "configs[2]: GPT-2-small MLP linears fc1 (3072x768) + fc2 (768x3072), "
-                               "8192 tokens, fp32 in/out, int8 SR forward, E5M2 SR backward; per layer "
-                               "5 absmax scales, 5 quantizers, 3 products",
-                   "tokens": TOKENS, "flop_per_step": 2 * 6.0 * TOKENS * 768 * 3072,
-                   "min_hbm_bytes_per_step": io_bytes},
+        "config": {"workload": "configs[3] at 65536 tokens: the seven linears of one Llama-1B-shaped decoder layer "
+                               "(q, k, v, o 2048x2048; gate, up 5632x2048; down 2048x5632), bf16 master weights, "
+                               "fp32 activations and gradients in and out, int4 SR on the output gradient and int8 SR "
+                               "on the other four quantizers; per linear 5 absmax scales, 5 quantizers, 3 products",
+                   "tokens": TOKENS, "flop_per_step": flops, "min_hbm_bytes_per_step": io_bytes},
         "frac_of_8bit_mfma_peak": round(tflops / MFMA_PEAK_TFLOPS["int8"], 4),
-        # the path's own ceiling: fp32 tensors in and out once per quantizer pass at HBM peak
-        "composite_ceiling_TFLOP/s": round(2 * 6.0 * TOKENS * 768 * 3072 / (io_bytes / (HBM_PEAK_GBS * 1e9)) / 1e12, 1),
+        # the path's own ceiling: every tensor in once per quantizer pass and every result out once
+        # at HBM peak, or the 8-bit MFMA peak, whichever is lower
+        "composite_ceiling_TFLOP/s": round(min(MFMA_PEAK_TFLOPS["int8"],
+                                               flops / (io_bytes / (HBM_PEAK_GBS * 1e9)) / 1e12), 1),
+        "per_shape": per_shape,
         "phases": phases,
-        "scales_given": {"value": round(result["given_scales"][1], 2), "unit": "TFLOP/s",
-                         "ms_per_step": round(result["given_scales"][0] * 1e3, 4),
-                         "note": "forward + backward entry points only (five quantizers, three products per "
-                                 "layer), the absmax passes left out: the scale is an input of the entry points"},
-        "f8_pipeline": {"value": round(result["f8_pipeline"][1], 2), "unit": "TFLOP/s",
-                        "ms_per_step": round(result["f8_pipeline"][0] * 1e3, 4),
-                        "frac_of_8bit_mfma_peak": round(result["f8_pipeline"][1] / MFMA_PEAK_TFLOPS["fp8"], 4),
-                        "note": "backward products on the fp8 matrix pipeline (hardware-truncated group sums, "
-                                "SRQ_FLAG_F8_PIPELINE)"},
-        "product_kernels": rl,
     }
-    dom = rl["f16"]
-    line["roofline"] = {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["TFLOP/s"], "peak": dom["peak"],
-                        "unit": "TFLOP/s", "frac": dom["frac"], "traffic": round(TRAFFIC_F16_PRODUCT_128),
-                        "note": "dominant kernel of the step by time (3 of its 6 products); 38.65 GFLOP per launch "
-                                "over the mean event-timed launch, which for the two weight-gradient launches "
-                                "includes the kernel that sums the three contraction slices; algorithmic bytes "
-                                "per launch %.1fe6 (operands once, result once), traffic = measured HBM bytes"
-                                % (ALGORITHMIC_F16_PRODUCT_128 / 1e6)}
-    if not args.no_quantizer_sweep:
+    line["roofline"] = llama_products_roofline(L, torch, max(5, args.steps // 2))
+    if not args.no_extras:
+        line["token_sweep"] = token_sweep(L, synth, torch)
+        line["gpt2_mlp"] = gpt2_mlp(L, synth, torch, args.steps, args.warmup)
         qs = quantizer_sweep(L, synth, torch, max(5, args.steps // 5))
         line["sr_quantize"] = qs
         line["roofline_quantizer"] = {"bound": "hbm", "kernel": "quantize_flat_f32_kernel<INT8, SR, byte> on 2^28 elements (5 B per element)",
                                       "achieved": qs["int8"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                       "frac": qs["int8"]["frac_of_hbm_peak"], "traffic": round(TRAFFIC_QUANTIZE_INT8_2P28)}
-    if args.train_step:
         line["train_step"] = train_step_times(torch)
-    if args.llama_sweep:
-        line["llama_linears"] = llama_sweep(L, synth, torch)
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)
@@ -417,7 +519,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(shapes)
+        line["cpu_baseline"] = cpu_baseline()
     print(json.dumps(line))
 
 
