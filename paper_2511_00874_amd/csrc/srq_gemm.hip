@@ -481,6 +481,300 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_kernel(GemmParams g, Sl
   }
 }
 
+// ---- 256 x 256 tiles, workgroups that stay -------------------------------------------------------
+// One workgroup per CU walks a list of tiles.  What that buys over one workgroup per tile:
+//   - the operand loads of the next tile's first stage are issued during the last stage of the
+//     current tile and land while its result is written, so no tile starts with an empty ring;
+//   - the result stores of tile i drain while tile i + 1 is multiplied.
+// The second point needs care on this chip: loads and stores of a wave share ONE in-order counter
+// (vmcnt), so a wave that has result stores in flight cannot wait for a later operand load without
+// waiting for those stores as well.  The waves are therefore given different memory duties, while
+// all eight multiply (wave tile 128 x 64):
+//   waves 0-3 ("loaders")  issue every operand DMA of the workgroup and never store to global
+//                          memory: their counter holds DMAs only, and waiting for a stage is exact;
+//   waves 4-7 ("storers")  issue every global store (the finished tile goes through LDS anyway, to
+//                          be written as whole rows) and never wait on the counter at all.
+// The ring has two stages of 64 KiB.  Stages are numbered through the whole tile list (`gs`): the
+// loaders issue stage gs + 1 -- the next stage of this tile, or the first of the next tile -- at
+// the barrier of stage gs, into the buffer that stage gs - 1 has just left.  When a tile is done,
+// the buffer of its last stage is the staging area of the epilogue (the other one is receiving the
+// next tile's first stage); it is handed back to the ring by the barrier of the next stage.
+// Every loop bound below is uniform over the workgroup, so all waves meet at every barrier.
+// The lane index again, as a value the optimiser cannot see through.  Address arithmetic that is
+// derived from it inside a loop is recomputed there (a few VALU operations) instead of being
+// hoisted out of the loop and held in registers across it: in the kernel below the accumulators and
+// operand fragments leave no room for that.
+__device__ __forceinline__ uint32_t opaque(uint32_t v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
+struct TileItem {
+  uint32_t valid, p0, q0, slice, kbeg, kend;
+};
+
+template <class MMA>
+__global__ __launch_bounds__(512) void gemm_nt_persist_kernel(GemmParams g, SliceSum rider) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  constexpr int BM = 256, BN = 256, WGN = 4, NW = 8, NLOAD = 4;
+  constexpr int WTM = 128, WTN = 64, TM = WTM / 32, TN = WTN / 32;
+  constexpr int STAGE = (BM + BN) * BK;
+  constexpr int XL = BM / 8 / NLOAD, ZL = BN / 8 / NLOAD;  // DMA instructions per loader wave and stage
+  static_assert(XL % 2 == 0 && ZL % 2 == 0, "row blocks of a wave must start at an even block");
+  static_assert(XL + ZL <= 63, "vmcnt range");
+  using acc_t = typename MMA::acc_t;
+  using frag_t = typename MMA::frag_t;
+  using raw_t = typename MMA::raw_t;
+  constexpr int FC = sizeof(raw_t) / 16;
+  constexpr int KSUB = BK / MMA::KSTEP;
+
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const bool loader = wave_u < NLOAD, storer = !loader;
+  const uint32_t wp = wave / WGN, wq = wave % WGN;
+  const uint32_t lds_base = (uint32_t)(size_t)(lds_void*)lds;
+
+  // Tile list of this workgroup.  As in gemm_nt_kernel, XCD x (workgroup ids = x mod 8) owns the
+  // contiguous range [x * chunk, (x + 1) * chunk) of the banded, slice-major tile order; its
+  // workgroups (slots) walk that range side by side, so the tiles in flight on one XCD at any time
+  // are neighbours and share operand panels in that L2.
+  constexpr uint32_t GROUP = 8;
+  const uint32_t ntiles = g.tiles_p * g.tiles_q, nwork = ntiles * g.nsplit, chunk = (nwork + 7u) >> 3;
+  const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3, nslots = gridDim.x >> 3;
+  const uint32_t range_end = min(nwork, (xcd + 1) * chunk);
+  auto item_at = [&](uint32_t n) {
+    TileItem it;
+    const uint32_t work = xcd * chunk + slot + n * nslots;
+    it.valid = work < range_end ? 1u : 0u;
+    const uint32_t w = it.valid ? work : 0u;
+    const uint32_t slice = w / ntiles, tile = w - slice * ntiles;
+    const uint32_t band = tile / (GROUP * g.tiles_q), band_p = band * GROUP;
+    const uint32_t band_rows = min(GROUP, g.tiles_p - band_p), in_band = tile - band * GROUP * g.tiles_q;
+    it.p0 = (band_p + in_band % band_rows) * BM;
+    it.q0 = (in_band / band_rows) * BN;
+    it.slice = slice;
+    it.kbeg = slice * g.k_per_split;
+    it.kend = min(g.R, it.kbeg + g.k_per_split);
+    return it;
+  };
+
+  const __amdgpu_buffer_rsrc_t xrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.X), 0, (int)(g.P * g.pitch), 0x00020000);
+  const __amdgpu_buffer_rsrc_t zrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.Z), 0, (int)(g.Q * g.pitch), 0x00020000);
+
+  // DMA addressing (LDS layout of a stage as in gemm_nt_kernel: 128-byte rows, 16-byte chunk c of
+  // row r at chunk c ^ ((r >> 1) & 7)); loader wave w fills tile rows [64 w, 64 w + 64) of X and of Z
+  auto issue = [&](const TileItem& it, int kt, uint32_t buf) {
+    const uint32_t ln = opaque(lane);
+    const uint32_t lrow = ln >> 3;
+    const uint32_t lchunk0 = (ln & 7u) ^ (ln >> 4), lchunk1 = lchunk0 ^ 4u;
+    const uint32_t xvoff = (it.p0 + wave * XL * 8 + lrow) * g.pitch + it.kbeg;
+    const uint32_t zvoff = (it.q0 + wave * ZL * 8 + lrow) * g.pitch + it.kbeg;
+    const uint32_t koff = (uint32_t)kt * BK;
+    const uint32_t kc0 = koff + lchunk0 * 16, kc1 = koff + lchunk1 * 16;
+    const bool live0 = it.kbeg + kc0 < it.kend, live1 = it.kbeg + kc1 < it.kend;
+    const uint32_t xs = lds_base + buf * STAGE + wave_u * XL * 1024;
+    const uint32_t zs = lds_base + buf * STAGE + BM * BK + wave_u * ZL * 1024;
+#pragma unroll
+    for (int i = 0; i < XL; ++i)
+      lds_dma16(xrsrc, xs + i * 1024,
+                (i & 1) ? (live1 ? xvoff + kc1 + i * 8 * g.pitch : OOB) : (live0 ? xvoff + kc0 + i * 8 * g.pitch : OOB));
+#pragma unroll
+    for (int i = 0; i < ZL; ++i)
+      lds_dma16(zrsrc, zs + i * 1024,
+                (i & 1) ? (live1 ? zvoff + kc1 + i * 8 * g.pitch : OOB) : (live0 ? zvoff + kc0 + i * 8 * g.pitch : OOB));
+  };
+
+  const uint32_t swz = ((lane >> 1) & 7u) ^ ((lane >> 5) * FC);
+  uint32_t xoff[KSUB * FC], zoff[KSUB * FC];
+#pragma unroll
+  for (int t = 0; t < KSUB * FC; ++t) {
+    const uint32_t tt = (t / FC) * 2 * FC + (t % FC);
+    xoff[t] = (wp * WTM + (lane & 31u)) * BK + ((swz ^ tt) << 4);
+    zoff[t] = BM * BK + (wq * WTN + (lane & 31u)) * BK + ((swz ^ tt) << 4);
+  }
+  auto load_frag = [&](const uint8_t* stage, const uint32_t (&off)[KSUB * FC], int sub, int ks) {
+    raw_t f;
+#pragma unroll
+    for (int c = 0; c < FC; ++c) {
+      const v4i part = *reinterpret_cast<const v4i*>(stage + off[ks * FC + c] + sub * 32 * BK);
+      f[4 * c + 0] = part[0]; f[4 * c + 1] = part[1]; f[4 * c + 2] = part[2]; f[4 * c + 3] = part[3];
+    }
+    return f;
+  };
+
+  acc_t acc[TM][TN];
+  constexpr int PF = KSUB > 2 ? 2 : 1;
+  auto compute = [&](uint32_t buf) {
+    const uint8_t* stage = lds + buf * STAGE;
+    raw_t xf[PF + 1][TM], zf[PF + 1][TN];
+    auto fetch = [&](int ks) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) xf[ks % (PF + 1)][i] = load_frag(stage, xoff, i, ks);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) zf[ks % (PF + 1)][j] = load_frag(stage, zoff, j, ks);
+    };
+#pragma unroll
+    for (int ks = 0; ks < PF && ks < KSUB; ++ks) fetch(ks);
+#pragma unroll
+    for (int ks = 0; ks < KSUB; ++ks) {
+      if (ks + PF < KSUB) fetch(ks + PF);
+      __builtin_amdgcn_sched_barrier(0);
+      frag_t xe[TM], ze[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) xe[i] = MMA::expand(xf[ks % (PF + 1)][i]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) ze[j] = MMA::expand(zf[ks % (PF + 1)][j]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = MMA::mma(ze[j], xe[i], acc[i][j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // Epilogue staging: every wave owns 8 KiB, a band of 32 p-rows x 64 q as rows of 256 bytes
+  // (16 chunks of 16 bytes); chunk c of row r is stored at chunk c ^ (r & 15), so that the
+  // sixteen lanes an LDS instruction serves together -- sixteen rows with one chunk index when
+  // the MFMA registers are written, sixteen chunks of one row when the rows are read back --
+  // always fall on sixteen different 16-byte slots of the 64 banks.
+  constexpr int EP_WAVE = 32 * WTN * 4;
+  static_assert(NW * EP_WAVE <= STAGE, "epilogue staging must fit in one ring buffer");
+  const float s = total_scale(g);
+  const bool q_vec = (g.Q & 3u) == 0;
+
+  TileItem cur = item_at(0);
+  uint32_t n_item = 0, gs = 0;
+  if (cur.valid) {
+    if (loader) issue(cur, 0, 0);
+    while (true) {
+      const TileItem nxt = item_at(++n_item);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+      const int ktiles = (int)((cur.kend - cur.kbeg + BK - 1) / BK);
+      for (int kt = 0; kt < ktiles; ++kt) {
+        if (loader) wait_vmcnt<0>();  // stage gs has landed (the only DMAs in flight)
+        __syncthreads();              // ... for every wave; and every wave has left stage gs - 1
+        if (loader) {
+          if (kt + 1 < ktiles) issue(cur, kt + 1, (gs + 1) & 1u);
+          else if (nxt.valid) issue(nxt, 0, (gs + 1) & 1u);
+        }
+        compute(gs & 1u);
+        ++gs;
+      }
+      __syncthreads();  // the buffer of the last stage is free: it stages the result
+      uint8_t* const stg = lds + ((gs - 1) & 1u) * STAGE;
+      uint32_t* const pbase = g.nsplit > 1 ? g.partial + (size_t)cur.slice * g.P * g.Q : nullptr;
+      // whole tile inside the output, rows 16-byte aligned, nothing to add to: plain row stores
+      const bool fast = q_vec && !g.accumulate && cur.p0 + BM <= g.P && cur.q0 + BN <= g.Q;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        if (i > 0) __syncthreads();  // the storers have read the previous band
+        // MFMA result register r of lane l: q = 8 (r / 4) + 4 (l / 32) + r % 4, p = l % 32.
+        // Final results are converted and scaled here, by the wave that computed them (all eight
+        // share that work); partial results of a slice go out as raw accumulator bits.
+        const uint32_t le = opaque(lane);
+        uint8_t* const mine = stg + wave_u * EP_WAVE + (le & 31u) * (WTN * 4);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            const uint32_t c = j * 8 + 2 * gq + (le >> 5);
+            v4u w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              w[e] = pbase ? MMA::bits(acc[i][j][4 * gq + e])
+                           : __float_as_uint(__fmul_rn(MMA::to_f32(acc[i][j][4 * gq + e]), s));
+            *reinterpret_cast<v4u*>(mine + ((c ^ (le & 15u)) << 4)) = w;
+          }
+        __syncthreads();
+        if (storer) {
+#pragma unroll 1
+          for (int h = 0; h < 2; ++h) {
+            const uint32_t src = (wave_u - NLOAD) * 2 + h;  // the wave whose band this is
+            const uint32_t pb = cur.p0 + (src / WGN) * WTM + i * 32, qw0 = cur.q0 + (src % WGN) * WTN;
+            const uint8_t* const band = stg + src * EP_WAVE;
+            const uint32_t ls = opaque(lane);
+            const uint32_t r4 = ls >> 4, c = ls & 15u;
+            if (fast) {
+              // EB row reads in flight, then EB stores of four whole 256-byte rows each
+              constexpr int EB = FC > 1 ? 4 : 8;  // (the pipeline with 32-byte fragments has fewer registers to spare)
+              uint32_t* const dst0 = (pbase ? pbase : reinterpret_cast<uint32_t*>(g.out)) +
+                                     (size_t)(pb + r4) * g.Q + qw0 + c * 4;
+#pragma unroll
+              for (int it0 = 0; it0 < 8; it0 += EB) {
+                v4u raw[EB];
+#pragma unroll
+                for (int it = 0; it < EB; ++it) {
+                  const uint32_t row = (it0 + it) * 4 + r4;
+                  raw[it] = *reinterpret_cast<const v4u*>(band + row * (WTN * 4) + ((c ^ (row & 15u)) << 4));
+                }
+#pragma unroll
+                for (int it = 0; it < EB; ++it) {
+                  uint32_t* const dst = dst0 + (size_t)(it0 + it) * 4 * g.Q;
+                  if (pbase) {
+                    // write-through: the partial tile does not stay dirty in the L2, and the sum
+                    // that reads it next still finds it in the last-level cache
+                    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(dst), "v"(raw[it]) : "memory");
+                  } else {
+                    // not read again by this kernel: a streaming store keeps it from pushing
+                    // operand panels out of the L2
+                    __builtin_nontemporal_store(raw[it], reinterpret_cast<v4u*>(dst));
+                  }
+                }
+              }
+            } else {
+#pragma unroll 2
+              for (int it = 0; it < 8; ++it) {
+                const uint32_t row = it * 4 + r4;
+                const v4u raw = *reinterpret_cast<const v4u*>(band + row * (WTN * 4) + ((c ^ (row & 15u)) << 4));
+                const uint32_t p = pb + row, q = qw0 + c * 4;
+                if (p >= g.P || q >= g.Q) continue;
+                const size_t idx = (size_t)p * g.Q + q;
+                if (pbase) {
+                  if (q_vec) {
+                    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(pbase + idx), "v"(raw) : "memory");
+                  } else {
+                    for (int e = 0; e < 4 && q + e < g.Q; ++e) pbase[idx + e] = raw[e];
+                  }
+                } else {
+                  float v[4];
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(raw[e]);
+                  float* dst = g.out + idx;
+                  if (q_vec) {
+                    if (g.accumulate) {
+                      const v4f o = *reinterpret_cast<const v4f*>(dst);
+#pragma unroll
+                      for (int e = 0; e < 4; ++e) v[e] = __fadd_rn(v[e], o[e]);
+                    }
+                    __builtin_nontemporal_store(v4f{v[0], v[1], v[2], v[3]}, reinterpret_cast<v4f*>(dst));
+                  } else {
+                    for (int e = 0; e < 4 && q + e < g.Q; ++e) dst[e] = g.accumulate ? __fadd_rn(v[e], dst[e]) : v[e];
+                  }
+                }
+              }
+            }
+          }
+        }
+      }
+      if (!nxt.valid) break;
+      cur = nxt;
+    }
+  }
+  // the slice sum of an earlier product, if this launch carries one: every workgroup takes a share
+  // once its tiles are done
+  if (rider.total > 0) {
+    if (rider.is_int) slice_sum<true>(rider, blockIdx.x, gridDim.x);
+    else slice_sum<false>(rider, blockIdx.x, gridDim.x);
+  }
+}
+
 // The slice sum in a launch of its own.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(SliceSum r) {
   if (r.is_int) slice_sum<true>(r, blockIdx.x, gridDim.x);
@@ -495,45 +789,58 @@ struct Plan {
 
 constexpr int NUM_CU = 256;
 
+// Tile shape and number of contraction slices by a cost model (seconds, for ranking only):
+//   time = rounds x (stages per item + fixed per-item stages) x operations per stage / rate
+//          + the pass over the partial results that every extra slice adds.
+// `rate` is what a CU sustains with that tile shape once its slots are full (measured, int8: the
+// other pipelines scale alike): 256 x 256 tiles on workgroups that stay run one per CU and hide
+// most of a tile's start and end; the 128-row tiles run two workgroups per CU (one alone gets
+// about 0.85 of the CU's rate); 64 x 64 is for problems too small for anything else.
+struct TileKind {
+  int tile, bm, bn, per_cu;
+  double rate_chip;   // operations per second over the whole chip, slots full
+  double fixed;       // start + end of an item, in stages
+};
+constexpr TileKind TILE_KINDS[] = {
+    {0, 256, 256, 1, 2.1e15, 6.0},
+    {1, 128, 128, 2, 1.45e15, 3.0},
+    {3, 128, 192, 2, 1.5e15, 3.0},
+    {2, 64, 64, 4, 0.5e15, 4.0},
+};
+constexpr double PARTIAL_BYTES_PER_SECOND = 4.0e12;  // partial tiles out and back in
+
 Plan make_plan(size_t P, size_t Q, size_t row_bytes) {
-  Plan pl;
-  auto tiles = [&](int bm, int bn) { return ((P + bm - 1) / bm) * ((Q + bn - 1) / bn); };
-  // 256 x 256 tiles halve the operand traffic per flop but leave one workgroup per CU; they
-  // pay off once there are several rounds of them.  The 128-row tiles run two workgroups per
-  // CU, which overlaps one group's output phase with the other's contraction; between
-  // 128 x 128 and 128 x 192 the one with fewer rounds of work over the CUs wins (8192 x 768
-  // is 384 tiles of the first, one and a half per CU, but exactly 256 of the second).
-  auto rounds_cost = [&](int bm, int bn) { return ((tiles(bm, bn) + NUM_CU - 1) / NUM_CU) * (size_t)bm * bn; };
-  if (tiles(256, 256) >= (size_t)NUM_CU * 2) { pl.tile = 0; pl.bm = 256; pl.bn = 256; }
-  else if (tiles(128, 128) >= (size_t)NUM_CU / 2) {
-    if (rounds_cost(128, 192) < rounds_cost(128, 128)) { pl.tile = 3; pl.bm = 128; pl.bn = 192; }
-    else { pl.tile = 1; pl.bm = 128; pl.bn = 128; }
-  }
-  else { pl.tile = 2; pl.bm = 64; pl.bn = 64; }
-  const size_t t = tiles(pl.bm, pl.bn);
   const size_t ksteps = (row_bytes + BK - 1) / BK;
-  size_t nsplit = 1;
-  if (t < (size_t)NUM_CU && ksteps >= 16) {
-    // Fewer tiles than CUs: cut the contraction into slices.  Cost of a choice, in stages of
-    // one workgroup alone on a CU: the busiest CU runs ceil(t * n / CUs) workgroups of
-    // ceil(stages / n) stages each; two resident workgroups together get about 1.4 times the
-    // rate of one; every slice adds a pass over the output (partial tile out, summed after),
-    // worth about 6 stages.  Keep at least 8 stages per slice.
-    size_t max_split = ksteps / 8;
+  Plan best{};
+  double best_time = 0.0;
+  bool have = false;
+  for (const TileKind& k : TILE_KINDS) {
+    const size_t t = ((P + k.bm - 1) / k.bm) * ((Q + k.bn - 1) / k.bn);
+    // slices only for long contractions (at least 8 stages each), at most 64
+    size_t max_split = ksteps >= 16 ? ksteps / 8 : 1;
     if (max_split > 64) max_split = 64;
-    double best = 0.0;
+    const double ops_stage = 2.0 * k.bm * k.bn * BK;
+    const double rate_cu = k.rate_chip / NUM_CU;
     for (size_t n = 1; n <= max_split; ++n) {
-      const size_t per_cu = (t * n + NUM_CU - 1) / NUM_CU;
-      double c = (double)(per_cu * ((ksteps + n - 1) / n));
-      if (per_cu >= 2) c /= 1.4;
-      if (n > 1) c += 6.0 * (double)n;
-      if (n == 1 || c < best) { best = c; nsplit = n; }
+      const size_t items = t * n, slots = (size_t)NUM_CU * k.per_cu;
+      const size_t rounds = (items + slots - 1) / slots;
+      const size_t stages = (ksteps + n - 1) / n;
+      // a workgroup's share of its CU: alone, or one of per_cu
+      const double share = items <= (size_t)NUM_CU ? (k.per_cu > 1 ? 0.85 : 1.0) : 1.0 / k.per_cu;
+      double time = (double)rounds * ((double)stages + k.fixed) * ops_stage / (rate_cu * share);
+      if (n > 1) time += 2.0 * (double)n * (double)P * (double)Q * 4.0 / PARTIAL_BYTES_PER_SECOND;
+      if (!have || time < best_time) {
+        have = true;
+        best_time = time;
+        best.tile = k.tile; best.bm = k.bm; best.bn = k.bn;
+        best.nsplit = (uint32_t)n;
+      }
     }
   }
-  const size_t steps_per = (ksteps + nsplit - 1) / nsplit;
-  pl.k_per_split = (uint32_t)(steps_per * BK);
-  pl.nsplit = (uint32_t)((ksteps + steps_per - 1) / steps_per);
-  return pl;
+  const size_t steps_per = (ksteps + best.nsplit - 1) / best.nsplit;
+  best.k_per_split = (uint32_t)(steps_per * BK);
+  best.nsplit = (uint32_t)((ksteps + steps_per - 1) / steps_per);
+  return best;
 }
 
 // What a launch is asked to do about slice sums: carry the one of an earlier product (`carry`,
@@ -590,9 +897,43 @@ hipError_t launch_tile(GemmParams g, const SliceSumPlan& ss, hipStream_t stream)
   return e;
 }
 
+// The 256 x 256 tiles on workgroups that stay (gemm_nt_persist_kernel): one workgroup per CU, or
+// fewer if there is less work.
+template <class MMA>
+hipError_t launch_persist(GemmParams g, const SliceSumPlan& ss, hipStream_t stream) {
+  constexpr int LDS_BYTES = 2 * (256 + 256) * BK;
+  auto kern = &gemm_nt_persist_kernel<MMA>;
+  static const hipError_t configured = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  if (configured != hipSuccess) return configured;
+  g.tiles_p = (g.P + 255) / 256;
+  g.tiles_q = (g.Q + 255) / 256;
+  const uint32_t nwork = g.tiles_p * g.tiles_q * g.nsplit, chunk = (nwork + 7) / 8;
+  const uint32_t slots = chunk < NUM_CU / 8 ? chunk : NUM_CU / 8;  // workgroups per XCD
+  SliceSum carry{};
+  if (ss.carry && ss.carry->total > 0) carry = *ss.carry;
+  kern<<<dim3(8 * slots), 512, LDS_BYTES, stream>>>(g, carry);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  SliceSum own{};
+  if (g.nsplit > 1) {
+    own.partial = g.partial; own.out = g.out; own.nsplit = g.nsplit; own.total = (size_t)g.P * g.Q;
+    own.s = GemmScale{g.alpha, g.sx, g.sz, g.sx_dev, g.sz_dev};
+    own.accumulate = g.accumulate;
+    own.is_int = std::is_same<typename MMA::acc_t, v16i>::value ? 1 : 0;
+  }
+  if (ss.defer) {
+    *ss.defer = own;
+  } else if (own.total > 0) {
+    splitk_reduce_kernel<<<slice_sum_blocks(own, 256, 4), 256, 0, stream>>>(own);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
 template <class MMA>
 hipError_t launch_mma(const GemmParams& g, const Plan& pl, const SliceSumPlan& ss, hipStream_t stream) {
-  if (pl.tile == 0) return launch_tile<MMA, 256, 256, 2, 4, 2>(g, ss, stream);  // 8 waves of 128 x 64
+  if (pl.tile == 0) return launch_persist<MMA>(g, ss, stream);                  // 8 waves of 128 x 64, persistent
   if (pl.tile == 1) return launch_tile<MMA, 128, 128, 2, 2, 2>(g, ss, stream);  // 4 waves of 64 x 64
   if (pl.tile == 3) return launch_tile<MMA, 128, 192, 2, 2, 2>(g, ss, stream);  // 4 waves of 64 x 96
   return launch_tile<MMA, 64, 64, 2, 2, 3>(g, ss, stream);

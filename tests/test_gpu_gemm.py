@@ -268,3 +268,54 @@ def test_fp8_pipeline_flag_same_codes_hardware_rounding():
     _run_layer(t, _quants(kinds, t, seed=5, flags=L.FLAG_F8_PIPELINE), f8_pipeline=True)
     t = _layer(2048, 768, 512, 4, std_dy=1e-3)
     _run_layer(t, _quants(kinds, t, seed=6, flags=L.FLAG_F8_PIPELINE), sample=20000, f8_pipeline=True)
+
+
+# Shapes that take the 256 x 256 tiles on workgroups that stay: ragged in both output dimensions
+# and in the contraction; more tiles than CUs (every workgroup walks several, the last ones fewer);
+# a contraction of one stage and of two (ring buffer parity at the tile change); a long contraction
+# cut into slices (partial tiles, ragged last slice).
+PERSIST_SHAPES = [(4104, 2056, 2064), (8200, 4104, 400), (8200, 4104, 144), (6160, 4104, 1040), (2056, 1032, 32784)]
+
+
+def _exact_on_device(X, Z, scale):
+    """Exact product of two int8 code matrices, in binary64 on the device (|sum| < 2^53)."""
+    return (X.view(torch.int8).double() @ Z.view(torch.int8).double().t()) * scale
+
+
+@pytest.mark.parametrize("P,Q,R", PERSIST_SHAPES)
+def test_large_tile_kernel_full_output_int8(P, Q, R):
+    say("gemm 256-tile int8", P, Q, R)
+    X, Z = _rand_codes((P, R), L.INT8, 5), _rand_codes((Q, R), L.INT4, 6)
+    Xd, Zd = to_dev(X), to_dev(Z)
+    got = L.sr_gemm_codes(Xd, L.INT8, Zd, L.INT4, alpha=0.5)
+    # every entry, against the exact integer product (no tile missing, none written twice wrongly)
+    assert torch.equal(got.double(), _exact_on_device(Xd, Zd, 0.5))
+    # and sampled entries against the oracle, edges of the tile grid included
+    rng = np.random.default_rng(1)
+    idx = np.concatenate([rng.integers(0, P * Q, size=4096).astype(np.uint64),
+                          np.array([0, Q - 1, (P - 1) * Q, P * Q - 1, 255 * Q + 255, 256 * Q + 256], dtype=np.uint64)])
+    ref = oracle.gemm_fwd(X, L.INT8, 1.0, Z, L.INT4, 0.5, at=idx)
+    assert np.array_equal(got.cpu().numpy().reshape(-1)[idx.astype(np.int64)], ref)
+    # beta = 1 adds to what is there
+    again = L.sr_gemm_codes(Xd, L.INT8, Zd, L.INT4, alpha=0.5, out=got.clone(), beta=1.0)
+    assert torch.equal(again.double(), 2 * _exact_on_device(Xd, Zd, 0.5))
+
+
+@pytest.mark.parametrize("P,Q,R", [(4104, 2056, 2064), (2056, 1032, 32784)])
+def test_large_tile_kernel_float_pipelines(P, Q, R):
+    say("gemm 256-tile e5m2", P, Q, R)
+    X, Z = _rand_codes((P, R), L.E5M2, 27), _rand_codes((Q, R), L.E5M2, 28)
+    Xd, Zd = to_dev(X), to_dev(Z)
+    rng = np.random.default_rng(2)
+    idx = np.concatenate([rng.integers(0, P * Q, size=4096).astype(np.uint64),
+                          np.array([0, Q - 1, (P - 1) * Q, P * Q - 1], dtype=np.uint64)])
+    ref, ab = oracle.gemm_fwd(X, L.E5M2, 0.5, Z, L.E5M2, 0.5, want_abs=True, at=idx)
+    pick = idx.astype(np.int64)
+    got = L.sr_gemm_e5m2(Xd, Zd, alpha=0.25).cpu().numpy().reshape(-1)[pick]      # f16 pipeline from codes
+    check_product(got, ref, ab, "e5m2 codes")
+    Xv = torch.from_numpy(oracle.decode_array(L.E5M2, X)).to(DEV).to(torch.bfloat16)
+    Zv = torch.from_numpy(oracle.decode_array(L.E5M2, Z)).to(DEV).to(torch.bfloat16)
+    got = L.sr_gemm_bf16(Xv, Zv, alpha=0.25).cpu().numpy().reshape(-1)[pick]       # bf16 pipeline
+    check_product(got, ref, ab, "bf16 values")
+    got = L.sr_gemm_codes(Xd, L.E5M2, Zd, L.E5M2, alpha=0.25).cpu().numpy().reshape(-1)[pick]  # fp8 pipeline
+    assert np.all(np.abs(got - ref) <= 7 * 2.0**-13 * ab)
