@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="headline step and its roofline only (for profiling runs)")
-    ap.add_argument("--only", default="", help="run only this extra section (profiling runs): gpt2, products")
+    ap.add_argument("--only", default="", help="run only this extra section (profiling runs): gpt2, products, fused")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB device copy (known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -180,7 +180,8 @@ def llama_products_roofline(L, torch, reps):
     tf = fl / (ms * 1e-3) / 1e12
     del calls
     torch.cuda.empty_cache()
-    return {"bound": "mfma", "kernel": "gemm_nt_kernel<I8Mma, 256, 256, ...> (int8 codes, int32 accumulators)",
+    return {"bound": "mfma", "kernel": "gemm_nt_persist_kernel<I8Mma> (int8 codes, int32 accumulators, 256 x 256 tiles "
+                                       "on workgroups that stay)",
             "achieved": round(tf, 1), "peak": MFMA_PEAK_TFLOPS["int8"], "unit": "TFLOP/s",
             "frac": round(tf / MFMA_PEAK_TFLOPS["int8"], 4), "traffic": TRAFFIC_I8_PRODUCT_LLAMA,
             "launches": len(shapes), "avg_launch_us": round(ms * 1e3, 2), "flop_per_launch": fl,
@@ -188,6 +189,49 @@ def llama_products_roofline(L, torch, reps):
             "note": "mean over the nine products (Y, dA, dW of the 2048x2048, 5632x2048 and 2048x5632 layers at "
                     "65536 tokens), operands already quantized; algorithmic bytes = both operands once + the "
                     "fp32 result once; the weight-gradient launches include the sum of their contraction slices"}
+
+
+def fused_prologue(L, synth, torch, reps):
+    """Forward product with the SR quantizers inside the product kernel (sr_linear_fwd_fused: source
+    tensors -> Eq. 1 -> LDS codes -> MFMA) against the quantize-once form (sr_linear_fwd with
+    SRQ_FLAG_QUANTIZE_ONCE: one launch writes the codes, a second multiplies), int8, scales given:
+    the small single layer, where the call selects the fused form, and the GPT-2 fc1 product, where
+    every element would be rounded again by 24 (A) or 64 (W) tiles."""
+    dev = "cuda:0"
+    out = {}
+    for name, (M, N, K) in (("single_layer_64x128x128", (64, 128, 128)), ("mid_128x128x768", (128, 128, 768)),
+                            ("gpt2_fc1_8192x3072x768", (8192, 3072, 768))):
+        A = synth.gaussian_torch((M, K), 1.0, 1, dev)
+        W = synth.gaussian_torch((N, K), 0.02, 2, dev)
+        sc = torch.empty(2, dtype=torch.float32, device=dev)
+        L.sr_absmax_scale(A, L.INT8, out=sc[0:1])
+        L.sr_absmax_scale(W, L.INT8, out=sc[1:2])
+        qA, qW = L.Quant(L.INT8, sc[0:1], 0, 0), L.Quant(L.INT8, sc[1:2], 0, 1 << 24)
+        qA_once = L.Quant(L.INT8, sc[0:1], 0, 0, flags=L.FLAG_QUANTIZE_ONCE)
+        Y = torch.empty((M, N), dtype=torch.float32, device=dev)
+        ws = torch.empty(L.sr_linear_workspace_bytes(L.OP_FWD, M, N, K) + 256, dtype=torch.uint8, device=dev)
+        once = event_ms(torch, lambda: L.sr_linear_fwd(A, W, qA_once, qW, out=Y, workspace=ws), reps, warm_ms=5.0)
+        fused = event_ms(torch, lambda: L.sr_linear_fwd_fused(A, W, qA, qW, out=Y), reps, warm_ms=5.0)
+        out[name] = {"quantize_once_us": round(once * 1e3, 1), "fused_us": round(fused * 1e3, 1)}
+    return out
+
+
+def vendor_int8_context(torch, reps):
+    """Context, not a target: the int8 x int8 -> int32 product of the ROCm BLAS library (through
+    torch._int_mm) on the three forward-product shapes of the headline step, same box, same run."""
+    dev = "cuda:0"
+    out = {}
+    for (P, Q, R) in ((TOKENS, 2048, 2048), (TOKENS, 5632, 2048), (TOKENS, 2048, 5632)):
+        X = torch.randint(-127, 128, (P, R), dtype=torch.int8, device=dev)
+        Zt = torch.randint(-127, 128, (Q, R), dtype=torch.int8, device=dev).t()
+        try:
+            ms = event_ms(torch, lambda: torch._int_mm(X, Zt), reps)
+            out["%dx%dx%d" % (P, Q, R)] = {"us": round(ms * 1e3, 1), "TOP/s": round(2.0 * P * Q * R / ms / 1e9, 1)}
+        except Exception as e:  # the routine is optional in a torch build
+            out["%dx%dx%d" % (P, Q, R)] = {"error": repr(e)[:120]}
+        del X, Zt
+    torch.cuda.empty_cache()
+    return out
 
 
 def token_sweep(L, synth, torch):
@@ -454,6 +498,9 @@ def main():
     if args.only == "gpt2":
         print(json.dumps({"gpt2_mlp": gpt2_mlp(L, synth, torch, args.steps, args.warmup)}))
         return
+    if args.only == "fused":
+        print(json.dumps({"fused_prologue": fused_prologue(L, synth, torch, 50)}))
+        return
     if args.only == "products":
         print(json.dumps({"roofline": llama_products_roofline(L, torch, max(5, args.steps // 2))}))
         return
@@ -510,6 +557,8 @@ def main():
         line["roofline_quantizer"] = {"bound": "hbm", "kernel": "quantize_flat_f32_kernel<INT8, SR, byte> on 2^28 elements (5 B per element)",
                                       "achieved": qs["int8"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                       "frac": qs["int8"]["frac_of_hbm_peak"], "traffic": round(TRAFFIC_QUANTIZE_INT8_2P28)}
+        line["fused_prologue"] = fused_prologue(L, synth, torch, 50)
+        line["vendor_int8_gemm_context"] = vendor_int8_context(torch, 5)
         line["train_step"] = train_step_times(torch)
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")

@@ -93,7 +93,7 @@ typedef struct {
   int32_t kind;            /* srq_kind                                                       */
   int32_t round;           /* srq_round                                                      */
   float scale;             /* Delta: finite, at least 2^-100 (1/scale * 2^16 stays finite)   */
-  uint32_t flags;          /* 0, or SRQ_FLAG_F8_PIPELINE | SRQ_FLAG_COUNTER_DEV (see below)  */
+  uint32_t flags;          /* 0, or a combination of the SRQ_FLAG_* bits below                */
   const float* scale_dev;  /* if not NULL: device pointer to the scale, read by the kernels  */
                            /* instead of `scale` (no host check is then possible)            */
   uint64_t seed;           /* Philox key                                                     */
@@ -122,7 +122,12 @@ enum { SRQ_FLAG_F8_PIPELINE = 1,
         * NULL) of a uint64 that holds it: the kernels read it when they run.  A launch recorded in a
         * HIP graph can then be replayed with fresh thresholds by updating that word on the device
         * between replays (by ceil(n/8) per tensor, as the host would advance the offset). */
-       SRQ_FLAG_COUNTER_DEV = 2 };
+       SRQ_FLAG_COUNTER_DEV = 2,
+       /* on either quantizer of sr_linear_fwd: keep the quantize-once form (operands rounded into the
+        * workspace by one launch, multiplied by a second) also where the call would round them inside
+        * the product kernel; the results are the same, the flag exists so that the two forms can be
+        * timed against each other.  Ignored everywhere else. */
+       SRQ_FLAG_QUANTIZE_ONCE = 4 };
 
 enum { SRQ_OP_FWD = 0, SRQ_OP_BWD_DATA = 1, SRQ_OP_BWD_WEIGHT = 2, SRQ_OP_BWD = 3, SRQ_OP_FWD_STASH = 4,
        SRQ_OP_BWD_STASHED = 5, SRQ_OP_FWD_WEIGHT_ONLY = 6, SRQ_OP_BWD_DATA_WEIGHT_ONLY = 7 };
@@ -192,6 +197,9 @@ size_t sr_gemm_e5m2_workspace_bytes(size_t P, size_t Q, size_t R);
 
 /* Forward pass, Alg. 1:  Y = Q(A; qA_fwd) Q(W; qW_fwd)^T.
  * M, N, K multiples of 16.  workspace: sr_linear_workspace_bytes(SRQ_OP_FWD, M, N, K).
+ * The operands are quantized once into the workspace and multiplied from there -- except for an
+ * integer pair with an output of at most four 64 x 64 tiles and K <= 256, which is rounded inside
+ * the product kernel (as sr_linear_fwd_fused; same result bit for bit, workspace untouched).
  * Weight-only objective (Sec. 3.2): with qA_fwd->kind == SRQ_NONE, Y = A Q(W; qW_fwd)^T with A
  * as it is: every product a * w_hat is exact and the sums are accumulated in binary32 (a
  * bfloat16 A is multiplied in place on the bf16 matrix pipeline, a binary32 A as three bfloat16
@@ -202,9 +210,22 @@ int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW
                   size_t N, size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* Alg. 1 with both quantizers inside the product kernel: every workgroup reads its tiles of A and
+ * W in their source precision, applies Eq. 1 (the thresholds of an element are fixed by its
+ * index, so the codes are the ones sr_quantize gives) and multiplies from LDS; no quantized
+ * operand is written to memory and no workspace is needed.  An element is rounded again by every
+ * output tile that uses it, so the call is meant for outputs of a few tiles (small M and N);
+ * on large shapes it is many times slower than sr_linear_fwd and exists there to be measured.
+ * Formats: qA_fwd and qW_fwd both integer (results equal to sr_linear_fwd bit for bit: the int32
+ * sums are exact), or both SRQ_E5M2 (exact products, binary32 sums; SRQ_FLAG_F8_PIPELINE is
+ * ignored); any other pair, and SRQ_NONE, is SRQ_ERR_UNSUPPORTED.  M, N, K multiples of 16. */
+int sr_linear_fwd_fused(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M,
+                        size_t N, size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd,
+                        void* stream);
+
 /* sr_linear_fwd for callers that cannot allocate device memory or pass a workspace: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
- * same kernels, same results bit for bit as sr_linear_fwd; the scratch (quantized operands,
+ * same kernels, same results bit for bit as sr_linear_fwd (it is that call); the scratch (quantized operands,
  * slice partials) is a static device array of SRQ_STATIC_SCRATCH_BYTES inside the library, one
  * copy per GPU, held until the process ends.  The call allocates nothing (no hipMalloc / hipFree,
  * no allocating runtime or library routine); the array's address is looked up once per device on

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsrq.so")
-SOURCES = ["srq_quantize.hip", "srq_quantize_jobs.hip", "srq_gemm.hip", "srq_update.hip", "srq_widen.hip", "srq_api.hip"]
+SOURCES = ["srq_quantize.hip", "srq_quantize_jobs.hip", "srq_gemm.hip", "srq_fused.hip", "srq_update.hip", "srq_widen.hip", "srq_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function",

@@ -129,6 +129,13 @@ hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint
 // a deferred slice sum that found no later launch to ride on
 hipError_t launch_slice_sum(const SliceSum& r, hipStream_t stream);
 
+// Alg. 1 with the quantizers inside the product kernel (srq_fused.hip): out (P x Q) =
+// Q(x)[P x R] . Q(z)[Q x R]^T from the source tensors, no codes in memory.  Formats: both integer,
+// or both E5M2.
+bool fused_pair_supported(int kind_x, int kind_z);
+hipError_t launch_fused_fwd(float* out, const void* x, const QuantArgs& qx, const void* z, const QuantArgs& qz,
+                            size_t P, size_t Q, size_t R, hipStream_t stream);
+
 inline bool kind_is_int(int k) { return k == SRQ_INT8 || k == SRQ_INT4; }
 // 8-bit float codes: E4M3, E5M2 and the sub-grids of E4M3 (stored as E4M3 codes)
 inline bool kind_is_f8(int k) { return k >= SRQ_E4M3 && k <= SRQ_E4M0; }

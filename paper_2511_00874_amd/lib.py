@@ -17,7 +17,7 @@ NONE, INT8, INT4, E4M3, E5M2, E4M2, E4M1, E4M0 = 0, 1, 2, 3, 4, 5, 6, 7
 SR, RTN = 0, 1
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD, OP_FWD_STASH, OP_BWD_STASHED = 0, 1, 2, 3, 4, 5
 OP_FWD_WEIGHT_ONLY, OP_BWD_DATA_WEIGHT_ONLY = 6, 7
-FLAG_F8_PIPELINE, FLAG_COUNTER_DEV = 1, 2
+FLAG_F8_PIPELINE, FLAG_COUNTER_DEV, FLAG_QUANTIZE_ONCE = 1, 2, 4
 KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2", E4M2: "e4m2", E4M1: "e4m1", E4M0: "e4m0"}
 QMAX = {INT8: 127.0, INT4: 7.0, E4M3: 448.0, E5M2: 57344.0, E4M2: 448.0, E4M1: 384.0, E4M0: 256.0}
 
@@ -58,6 +58,7 @@ _lib.sr_gemm_e5m2_workspace_bytes.restype = _sz
 _lib.sr_linear_fwd.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _vp, _sz, _vp]
 _lib.sr_linear_bwd_data.argtypes = _lib.sr_linear_fwd.argtypes
 _lib.sr_linear_fwd_static.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _vp]
+_lib.sr_linear_fwd_fused.argtypes = _lib.sr_linear_fwd_static.argtypes
 _lib.sr_linear_fwd_static_limit.argtypes = []
 _lib.sr_linear_fwd_static_limit.restype = _sz
 _lib.sr_linear_bwd_weight.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp,
@@ -73,14 +74,15 @@ _lib.sr_linear_bwd_stashed.argtypes = [_vp, _vp, _vp, C.c_int, _sz, _sz, _sz, _q
 _lib.sr_update_bf16.argtypes = [_vp, _vp, C.c_float, _sz, C.c_int, C.c_uint64, C.c_uint64, _vp]
 _lib.sr_status_string.argtypes = [C.c_int]
 _lib.sr_status_string.restype = C.c_char_p
-for _n in ("sr_linear_fwd_static", "sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_gemm_e5m2", "sr_linear_fwd", "sr_linear_bwd_data",
+for _n in ("sr_linear_fwd_static", "sr_linear_fwd_fused", "sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_gemm_e5m2", "sr_linear_fwd", "sr_linear_bwd_data",
            "sr_linear_bwd_weight", "sr_linear_bwd", "sr_update_bf16", "sr_linear_fwd_stash", "sr_linear_bwd_stashed"):
     getattr(_lib, _n).restype = C.c_int
 
 EXPORTS = ["sr_absmax_scale", "sr_absmax_scales", "sr_absmax_workspace_bytes", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes", "sr_gemm_bf16", "sr_gemm_bf16_workspace_bytes", "sr_gemm_e5m2", "sr_gemm_e5m2_workspace_bytes",
            "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight", "sr_linear_bwd",
            "sr_linear_workspace_bytes", "sr_linear_stash_bytes", "sr_linear_fwd_stash", "sr_linear_bwd_stashed",
-           "sr_update_bf16", "sr_status_string", "sr_linear_fwd_static", "sr_linear_fwd_static_limit"]
+           "sr_update_bf16", "sr_status_string", "sr_linear_fwd_static", "sr_linear_fwd_static_limit",
+           "sr_linear_fwd_fused"]
 
 raw = _lib  # the C entry points themselves, for tests of the error paths
 
@@ -308,6 +310,17 @@ def sr_linear_fwd_static(A, W, qA, qW, out):
     N = W.shape[0]
     _check(_lib.sr_linear_fwd_static(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K,
                                      C.byref(qA.c()), C.byref(qW.c()), _stream()))
+    return out
+
+
+def sr_linear_fwd_fused(A, W, qA, qW, out=None):
+    """Alg. 1 with the quantizers inside the product kernel (no workspace, no codes in memory)."""
+    M, K = A.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    _check(_lib.sr_linear_fwd_fused(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K,
+                                    C.byref(qA.c()), C.byref(qW.c()), _stream()))
     return out
 
 

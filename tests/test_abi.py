@@ -64,7 +64,7 @@ def test_quantize_argument_checks(lib):
     assert r.sr_quantize(buf, buf, 7, 4, 8, 0, C.byref(_q(lib)), None) == -3
     for bad in (0.0, -1.0, float("inf"), float("nan"), 1e-45):
         assert r.sr_quantize(buf, buf, 0, 4, 8, 0, C.byref(_q(lib, scale=bad)), None) == -3
-    assert r.sr_quantize(buf, buf, 0, 4, 8, 0, C.byref(_q(lib, flags=4)), None) == -3
+    assert r.sr_quantize(buf, buf, 0, 4, 8, 0, C.byref(_q(lib, flags=8)), None) == -3
     assert r.sr_quantize(buf, buf, 0, 4, 8, 0, C.byref(_q(lib, flags=2)), None) == -4    # device counter: NULL address
     assert r.sr_quantize(buf, buf + 4, 0, 4, 8, 0, C.byref(_q(lib)), None) == -4
     assert r.sr_quantize(buf, buf, 0, 4, 12, 1, C.byref(_q(lib)), None) == -4       # cols % 8

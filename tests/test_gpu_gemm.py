@@ -261,6 +261,24 @@ def test_llama_projection_at_65536_tokens_sampled():
         _run_layer(t, _quants(kinds, t, seed=4), sample=16384)
 
 
+def test_llama_mlp_shapes_at_65536_tokens_sampled():
+    # the benchmark's largest products: gate / up (5632 x 2048) and down (2048 x 5632) at 65536 tokens
+    kinds = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.INT8, "W_bwd": L.INT8, "dY_bwd": L.INT4}
+    for N, K in ((5632, 2048), (2048, 5632)):
+        t = _layer(65536, N, K, 24, std_dy=1e-3, w_bf16=True)
+        _run_layer(t, _quants(kinds, t, seed=6), sample=8192)
+        del t
+        torch.cuda.empty_cache()
+
+
+def test_decoder_lm_head_shape_sampled():
+    # the widest linear of the 12-layer decoder (vocabulary 32000, d = 768) at 8 x 1024 tokens, in the
+    # formats of its training step
+    kinds = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.E5M2, "W_bwd": L.E5M2, "dY_bwd": L.E5M2}
+    t = _layer(8192, 32000, 768, 25, std_dy=1e-3, w_bf16=True)
+    _run_layer(t, _quants(kinds, t, seed=7), sample=16384)
+
+
 def test_fp8_pipeline_flag_same_codes_hardware_rounding():
     # the fp8 matrix pipeline: same quantized operands, products within the hardware's bound
     kinds = {"A_fwd": L.E4M3, "W_fwd": L.E4M3, "A_bwd": L.E5M2, "W_bwd": L.E5M2, "dY_bwd": L.E5M2}

@@ -1,0 +1,84 @@
+"""The quantized operands the linear entry points leave in the caller's workspace, compared bit for
+bit with the oracle's codes: these come from the kernel that quantizes all operands of a call in one
+launch (same-layout, transposing, two-output and bfloat16-valued forms), not from sr_quantize.
+
+Workspace layout (pieces aligned to 256 bytes): forward  [Q(A) M x K | Q(W) N x K | slices];
+whole backward pass  [Q(dY) M x N | Q(W)^T K x N | slices | Q(dY)^T N x M | Q(A)^T K x M | slices].
+An operand is one byte per element (integer formats: the value, int4 too; E5M2 when every operand
+of the call is E5M2: the code) or the grid value as bfloat16."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_00874_amd import lib as L
+from paper_2511_00874_amd import synth
+from gpu_util import KINDS, host_src, say, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _up(n):
+    return (n + 255) // 256 * 256
+
+
+def _form(kind):
+    """(element size, slice-workspace query) of the stored form when all operands have this kind."""
+    if kind in (L.INT8, L.INT4):
+        return 1, lambda P, Q, R: L.sr_gemm_workspace_bytes(P, Q, R)
+    if kind == L.E5M2:
+        return 1, lambda P, Q, R: L.raw.sr_gemm_e5m2_workspace_bytes(P, Q, R)
+    return 2, lambda P, Q, R: L.raw.sr_gemm_bf16_workspace_bytes(P, Q, R)
+
+
+def _expect(t, kind, q, transpose, es):
+    codes = oracle.quantize(host_src(t), kind, q.scale, q.seed, q.counter_offset)
+    if transpose:
+        codes = np.ascontiguousarray(codes.T)
+    if es == 1:
+        return codes.reshape(-1)
+    vals = oracle.decode_array(kind, codes).astype(np.float32)   # every grid value is a bfloat16 number
+    return torch.from_numpy(vals).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint8).reshape(-1)
+
+
+def _piece(ws, off, n):
+    return ws[off:off + n].cpu().numpy()
+
+
+def _run(M, N, K, kind, seed, w_bf16):
+    A, W, dY = synth.single_layer(M, N, K, seed, std_dy=1e-3)
+    A, W, dY = to_dev(A), to_dev(W, w_bf16), to_dev(dY)
+    qs, off = {}, 0
+    for name, t in (("A_fwd", A), ("W_fwd", W), ("dY", dY), ("W_bwd", W), ("A_bwd", A)):
+        qs[name] = oracle.Quant(kind, oracle.absmax_scale(host_src(t), kind), seed, off)
+        off += (t.numel() + 7) // 8
+    lq = {n: L.Quant(kind, q.scale, q.seed, q.counter_offset) for n, q in qs.items()}
+    es, slices = _form(kind)
+
+    ws = torch.zeros(L.sr_linear_workspace_bytes(L.OP_FWD, M, N, K), dtype=torch.uint8, device=A.device)
+    L.sr_linear_fwd(A, W, lq["A_fwd"], lq["W_fwd"], workspace=ws)
+    assert np.array_equal(_piece(ws, 0, M * K * es), _expect(A, kind, qs["A_fwd"], False, es)), "Q(A) forward"
+    assert np.array_equal(_piece(ws, _up(M * K * es), N * K * es), _expect(W, kind, qs["W_fwd"], False, es)), "Q(W) forward"
+
+    ws = torch.zeros(L.sr_linear_workspace_bytes(L.OP_BWD, M, N, K), dtype=torch.uint8, device=A.device)
+    L.sr_linear_bwd(dY, W, A, lq["dY"], lq["W_bwd"], lq["A_bwd"], workspace=ws)
+    o_dy = 0
+    o_wt = o_dy + _up(M * N * es)
+    o_dyt = o_wt + _up(K * N * es) + _up(slices(M, K, N))
+    o_at = o_dyt + _up(N * M * es)
+    assert np.array_equal(_piece(ws, o_dy, M * N * es), _expect(dY, kind, qs["dY"], False, es)), "Q(dY)"
+    assert np.array_equal(_piece(ws, o_wt, K * N * es), _expect(W, kind, qs["W_bwd"], True, es)), "Q(W)^T"
+    assert np.array_equal(_piece(ws, o_dyt, N * M * es), _expect(dY, kind, qs["dY"], True, es)), "Q(dY)^T"
+    assert np.array_equal(_piece(ws, o_at, K * M * es), _expect(A, kind, qs["A_bwd"], True, es)), "Q(A)^T"
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_ragged_layer_every_format(kind):
+    say("workspace codes", L.KIND_NAMES[kind])
+    _run(272, 144, 208, kind, seed=3, w_bf16=True)
+
+
+@pytest.mark.parametrize("kind", [L.INT8, L.E5M2])
+def test_gpt2_fc1_benchmark_formats(kind):
+    say("workspace codes fc1", L.KIND_NAMES[kind])
+    _run(8192, 3072, 768, kind, seed=10, w_bf16=False)
