@@ -182,34 +182,38 @@ __device__ __forceinline__ uint32_t abs_bits_finite(float f) {
   return a < 0x7F800000u ? a : 0u;
 }
 
-// max of the finite |x_i| bit patterns over the elements this thread takes of x[0, n): thread
-// `tid` of `nthreads`, 16-byte loads that are contiguous across the wave (the order of the
-// elements does not matter for a maximum)
+// max of the finite |x_i| bit patterns over the 16-byte pieces [g0, g1) of x (4 binary32 or 8
+// bfloat16 elements each; the last piece of the tensor may be partial): thread t of nt, four loads in
+// flight per lane, the pieces of a workgroup contiguous in memory
 template <int SRC>
-__device__ __forceinline__ uint32_t absmax_slice(const void* __restrict__ x, size_t n, size_t tid, size_t nthreads) {
+__device__ __forceinline__ uint32_t absmax_pieces(const void* __restrict__ x, size_t n, size_t g0, size_t g1, uint32_t t,
+                                                  uint32_t nt) {
+  constexpr int PER = SRC == SRQ_F32 ? 4 : 8;
   uint32_t m = 0u;
-  if constexpr (SRC == SRQ_F32) {
-    const f32x4* p = static_cast<const f32x4*>(x);
-    const size_t n4 = n / 4;
-    auto fold = [&](const f32x4& a) {
-      m = max(max(m, max(abs_bits_finite(a.x), abs_bits_finite(a.y))), max(abs_bits_finite(a.z), abs_bits_finite(a.w)));
-    };
-    size_t i = tid;
-    for (; i + 3 * nthreads < n4; i += 4 * nthreads) {  // four loads in flight per lane
-      const f32x4 a = __builtin_nontemporal_load(p + i), b = __builtin_nontemporal_load(p + i + nthreads);
-      const f32x4 c = __builtin_nontemporal_load(p + i + 2 * nthreads), d = __builtin_nontemporal_load(p + i + 3 * nthreads);
-      fold(a); fold(b); fold(c); fold(d);
-    }
-    for (; i < n4; i += nthreads) fold(__builtin_nontemporal_load(p + i));
-    if (tid < n - n4 * 4) m = max(m, abs_bits_finite(static_cast<const float*>(x)[n4 * 4 + tid]));
-  } else {
-    const size_t ngroups = (n + 7) / 8;
-    for (size_t g = tid; g < ngroups; g += nthreads) {
-      float v[8];
-      load_group<SRQ_BF16>(v, x, g, n);
+  const size_t full = n / PER;  // pieces that lie wholly inside the tensor
+  const size_t gf = g1 < full ? g1 : full;
+  const u32x4* p = static_cast<const u32x4*>(x);
+  auto fold = [&](const u32x4& a) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) m = max(m, abs_bits_finite(v[j]));
+    for (int j = 0; j < 4; ++j) {
+      if constexpr (SRC == SRQ_F32) {
+        m = max(m, abs_bits_finite(__uint_as_float(a[j])));
+      } else {
+        m = max(m, max(abs_bits_finite(bf16_to_f32(a[j] & 0xFFFFu)), abs_bits_finite(bf16_to_f32(a[j] >> 16))));
+      }
     }
+  };
+  size_t i = g0 + t;
+  for (; i + 3 * (size_t)nt < gf; i += 4 * (size_t)nt) {
+    const u32x4 a = __builtin_nontemporal_load(p + i), b = __builtin_nontemporal_load(p + i + nt);
+    const u32x4 c = __builtin_nontemporal_load(p + i + 2 * (size_t)nt), d = __builtin_nontemporal_load(p + i + 3 * (size_t)nt);
+    fold(a); fold(b); fold(c); fold(d);
+  }
+  for (; i < gf; i += nt) fold(__builtin_nontemporal_load(p + i));
+  if (g1 > full && t < n - full * PER) {  // the partial last piece, element by element
+    const size_t e = full * PER + t;
+    m = max(m, abs_bits_finite(SRC == SRQ_F32 ? static_cast<const float*>(x)[e]
+                                              : bf16_to_f32(static_cast<const uint16_t*>(x)[e])));
   }
   return m;
 }
@@ -223,7 +227,11 @@ __global__ void absmax_init_kernel(uint32_t* acc) { *acc = 0u; }
 template <int SRC>
 __global__ __launch_bounds__(QBLOCK) void absmax_kernel(uint32_t* __restrict__ acc,
                                                         const void* __restrict__ x, size_t n) {
-  uint32_t m = absmax_slice<SRC>(x, n, (size_t)blockIdx.x * QBLOCK + threadIdx.x, (size_t)gridDim.x * QBLOCK);
+  // every workgroup one contiguous share of the tensor
+  constexpr size_t PER = SRC == SRQ_F32 ? 4 : 8;
+  const size_t pieces = (n + PER - 1) / PER, share = (pieces + gridDim.x - 1) / gridDim.x;
+  const size_t g0 = (size_t)blockIdx.x * share, g1 = g0 + share < pieces ? g0 + share : pieces;
+  uint32_t m = g0 < pieces ? absmax_pieces<SRC>(x, n, g0, g1, threadIdx.x, QBLOCK) : 0u;
   m = wave_umax(m);
   __shared__ uint32_t part[QBLOCK / 64];
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
@@ -242,9 +250,10 @@ __global__ void absmax_finish_kernel(float* scale, float qmax) {
 }
 
 // ---- several tensors, several scales, two launches -----------------------------------------
-// Launch 1: every block reduces one slice of one tensor and writes its partial maximum to the
-// workspace (plain stores: nothing to initialise).  Launch 2: one block folds the partials of
-// each tensor and writes the requested scales (several formats may share one tensor).
+// Launch 1: every block reduces one contiguous slice of one tensor and writes its partial maximum
+// to the workspace (plain stores: nothing to initialise).  Launch 2: one block per tensor folds
+// that tensor's partials and writes the scales requested of it (several formats may share one
+// tensor).
 __global__ __launch_bounds__(QBLOCK) void absmax_multi_kernel(AbsmaxBatch b) {
   int t = 0;
 #pragma unroll
@@ -253,9 +262,13 @@ __global__ __launch_bounds__(QBLOCK) void absmax_multi_kernel(AbsmaxBatch b) {
   const uint32_t local = blockIdx.x - b.first_block[t], nblk = b.nblocks[t];
   const size_t n = b.n[t];
   const void* x = b.x[t];
-  const size_t tid = (size_t)local * QBLOCK + threadIdx.x, nthreads = (size_t)nblk * QBLOCK;
-  uint32_t m = b.dtype[t] == SRQ_F32 ? absmax_slice<SRQ_F32>(x, n, tid, nthreads)
-                                     : absmax_slice<SRQ_BF16>(x, n, tid, nthreads);
+  const size_t per = b.dtype[t] == SRQ_F32 ? 4 : 8;
+  const size_t pieces = (n + per - 1) / per, share = (pieces + nblk - 1) / nblk;
+  const size_t g0 = (size_t)local * share, g1 = g0 + share < pieces ? g0 + share : pieces;
+  uint32_t m = 0u;
+  if (g0 < pieces)
+    m = b.dtype[t] == SRQ_F32 ? absmax_pieces<SRQ_F32>(x, n, g0, g1, threadIdx.x, QBLOCK)
+                              : absmax_pieces<SRQ_BF16>(x, n, g0, g1, threadIdx.x, QBLOCK);
   m = wave_umax(m);
   __shared__ uint32_t part[QBLOCK / 64];
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
@@ -268,24 +281,24 @@ __global__ __launch_bounds__(QBLOCK) void absmax_multi_kernel(AbsmaxBatch b) {
   }
 }
 
-__global__ __launch_bounds__(QBLOCK) void absmax_multi_finish_kernel(AbsmaxBatch b) {
-  __shared__ uint32_t part[QBLOCK / 64];
-  __shared__ uint32_t tmax[ABSMAX_MAX];
-  for (int t = 0; t < b.ntensors; ++t) {
-    uint32_t m = 0u;
-    for (uint32_t i = threadIdx.x; i < b.nblocks[t]; i += QBLOCK) m = max(m, b.partial[b.first_block[t] + i]);
-    m = wave_umax(m);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t r = part[0];
-      for (int i = 1; i < QBLOCK / 64; ++i) r = max(r, part[i]);
-      tmax[t] = r;
-    }
-    __syncthreads();
-  }
-  if ((int)threadIdx.x < b.nouts) {
-    const float amax = __uint_as_float(tmax[b.out_tensor[threadIdx.x]]);
+constexpr int FINISH_BLOCK = 1024;
+__global__ __launch_bounds__(FINISH_BLOCK) void absmax_multi_finish_kernel(AbsmaxBatch b) {
+  __shared__ uint32_t part[FINISH_BLOCK / 64];
+  const int t = blockIdx.x;  // one block per tensor
+  const uint32_t* p = b.partial + b.first_block[t];
+  const uint32_t nb = b.nblocks[t];
+  uint32_t m = 0u;
+  uint32_t i = threadIdx.x;
+  for (; i + 3 * FINISH_BLOCK < nb; i += 4 * FINISH_BLOCK)
+    m = max(max(m, max(p[i], p[i + FINISH_BLOCK])), max(p[i + 2 * FINISH_BLOCK], p[i + 3 * FINISH_BLOCK]));
+  for (; i < nb; i += FINISH_BLOCK) m = max(m, p[i]);
+  m = wave_umax(m);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if ((int)threadIdx.x < b.nouts && b.out_tensor[threadIdx.x] == t) {
+    uint32_t r = part[0];
+    for (int w = 1; w < FINISH_BLOCK / 64; ++w) r = max(r, part[w]);
+    const float amax = __uint_as_float(r);
     *b.out[threadIdx.x] = amax == 0.0f ? 1.0f : fmaxf(__fdiv_rn(amax, b.out_qmax[threadIdx.x]), MIN_SCALE);
   }
 }
@@ -403,7 +416,7 @@ hipError_t launch_absmax_batch(AbsmaxBatch& b, hipStream_t stream) {
   const size_t blocks = absmax_batch_plan(b);
   for (int i = 0; i < b.nouts; ++i) b.out_qmax[i] = qmax_of(b.out_kind[i]);
   absmax_multi_kernel<<<(unsigned)blocks, QBLOCK, 0, stream>>>(b);
-  absmax_multi_finish_kernel<<<1, QBLOCK, 0, stream>>>(b);
+  absmax_multi_finish_kernel<<<b.ntensors, FINISH_BLOCK, 0, stream>>>(b);
   return hipGetLastError();
 }
 
