@@ -25,10 +25,10 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"int8": 5000.0, "fp8": 5000.0, "bf16": 2500.0, "fp16": 2500.0}
 TOKENS = 65536
 GPT2_TOKENS = 8192
-# HBM bytes per launch of the dominant kernel (int8 product, 256 x 256 tiles) on the nine products of
-# the headline workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by what the same counters
-# read for a plain copy of known size (profiles/llama_hbm_traffic.txt); None until measured
-TRAFFIC_I8_PRODUCT_LLAMA = None
+# Bytes moved behind the L2 per launch of the dominant kernel (int8 product, 256 x 256 tiles) on the nine
+# products of the headline workload, slice sums included: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by
+# what the same counters read for a plain copy of known size (profiles/product_int8_llama_hbm_traffic.txt)
+TRAFFIC_I8_PRODUCT_LLAMA = 1656348073
 TRAFFIC_QUANTIZE_INT8_2P28 = (1024.0 + 256.0) * 2**20
 
 
@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="headline step and its roofline only (for profiling runs)")
-    ap.add_argument("--only", default="", help="run only this extra section (profiling runs): gpt2, products, fused")
+    ap.add_argument("--only", default="", help="run only this section (profiling runs): gpt2, products, fused, quantizer")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB device copy (known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -495,14 +495,29 @@ def main():
         print("bench.py needs a GPU (there is no CPU path)", file=sys.stderr)
         sys.exit(2)
 
-    if args.only == "gpt2":
-        print(json.dumps({"gpt2_mlp": gpt2_mlp(L, synth, torch, args.steps, args.warmup)}))
-        return
-    if args.only == "fused":
-        print(json.dumps({"fused_prologue": fused_prologue(L, synth, torch, 50)}))
-        return
-    if args.only == "products":
-        print(json.dumps({"roofline": llama_products_roofline(L, torch, max(5, args.steps // 2))}))
+    def calibrate_copy():
+        # a plain device copy of 2^28 floats: 1 GiB read, 1 GiB written
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    if args.only:
+        if args.only == "gpt2":
+            out = {"gpt2_mlp": gpt2_mlp(L, synth, torch, args.steps, args.warmup)}
+        elif args.only == "fused":
+            out = {"fused_prologue": fused_prologue(L, synth, torch, 50)}
+        elif args.only == "quantizer":
+            out = {"sr_quantize": quantizer_sweep(L, synth, torch, max(5, args.steps // 5))}
+        elif args.only == "products":
+            out = {"roofline": llama_products_roofline(L, torch, max(5, args.steps // 2))}
+        else:
+            print("unknown section " + args.only, file=sys.stderr)
+            sys.exit(2)
+        if args.calibrate_copy:
+            calibrate_copy()
+        print(json.dumps(out))
         return
 
     layers = llama_layers(L, synth, torch, TOKENS, synth.LLAMA_1B_LINEARS)
@@ -561,12 +576,7 @@ def main():
         line["vendor_int8_gemm_context"] = vendor_int8_context(torch, 5)
         line["train_step"] = train_step_times(torch)
     if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline()
     print(json.dumps(line))
