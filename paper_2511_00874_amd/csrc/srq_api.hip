@@ -517,6 +517,7 @@ int sr_linear_fwd_fused(float* Y, const void* A, int dtypeA, const void* W, int 
   if (!aligned16(Y)) return SRQ_ERR_ALIGN;
   if (!fused_pair_supported(qA_fwd->kind, qW_fwd->kind)) return SRQ_ERR_UNSUPPORTED;
   if (!int_contraction_ok(qA_fwd->kind, K)) return SRQ_ERR_UNSUPPORTED;
+  if (((M + 127) / 128) * ((N + 127) / 128) > 0x7FFFFFFFull) return SRQ_ERR_UNSUPPORTED;  // one workgroup per tile
   return launch_fused_fwd(Y, A, make_args(qA_fwd, dtypeA, STORE_BYTE), W, make_args(qW_fwd, dtypeW, STORE_BYTE), M, N,
                           K, static_cast<hipStream_t>(stream)) == hipSuccess
              ? SRQ_OK

@@ -120,6 +120,15 @@ def test_linear_argument_checks(lib):
     assert r.sr_linear_fwd(*args, 64, 128, 128, C.byref(q0), C.byref(q8), buf, 16, None) == -5
     assert r.sr_linear_fwd(*args, 64, 128, 120, C.byref(q0), C.byref(q8), buf, ws, None) == -4
     assert r.sr_linear_bwd_data(None, buf, 0, buf, 0, 64, 128, 128, C.byref(q0), C.byref(q8), buf, ws, None) == -1
+    # the forward product with the quantizers inside it: integer pairs or E5M2 pairs, no workspace
+    assert r.sr_linear_fwd_fused(*args, 64, 128, 128, C.byref(qf), C.byref(qf), None) == -6
+    assert r.sr_linear_fwd_fused(*args, 64, 128, 128, C.byref(q8), C.byref(q52), None) == -6
+    assert r.sr_linear_fwd_fused(*args, 64, 128, 128, C.byref(q0), C.byref(q8), None) == -6
+    assert r.sr_linear_fwd_fused(*args, 64, 128, 120, C.byref(q8), C.byref(q8), None) == -4
+    assert r.sr_linear_fwd_fused(None, buf, 0, buf, 0, 64, 128, 128, C.byref(q8), C.byref(q8), None) == -1
+    assert r.sr_linear_fwd_fused(*args, 1 << 31, 1 << 31, 16, C.byref(q8), C.byref(q8), None) == -6
+    # SRQ_FLAG_QUANTIZE_ONCE is a known flag
+    assert r.sr_linear_fwd(*args, 64, 128, 128, C.byref(_q(lib, 1, flags=4)), C.byref(q8), None, 0, None) == -5
     assert r.sr_gemm_codes(buf, buf, 1, buf, 3, 16, 16, 16, 1.0, 0.0, None, 0, None) == -6
     assert r.sr_gemm_codes(buf, buf, 1, buf, 1, 16, 16, 24, 1.0, 0.0, None, 0, None) == -4
 
