@@ -80,8 +80,10 @@ class Layer:
         self.Y = torch.empty((M, N), dtype=torch.float32, device=dev)
         self.dA = torch.empty((M, K), dtype=torch.float32, device=dev)
         self.dW = torch.empty((N, K), dtype=torch.float32, device=dev)
-        need = max(L.sr_linear_workspace_bytes(op, M, N, K) for op in (L.OP_FWD, L.OP_BWD))
-        self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        # forward and backward operands in workspaces of their own: the backward operands of a layer can
+        # then be rounded while its forward product still reads the forward ones
+        self.ws = torch.empty(L.sr_linear_workspace_bytes(L.OP_FWD, M, N, K), dtype=torch.uint8, device=dev)
+        self.ws_bwd = torch.empty(L.sr_linear_workspace_bytes(L.OP_BWD, M, N, K), dtype=torch.uint8, device=dev)
         self.absmax = L.AbsmaxBatch([(t, kind, s) for t, kind, s in self.src_of.values()])
 
     def step(self, L):
@@ -96,9 +98,12 @@ class Layer:
     def forward(self, L):
         L.sr_linear_fwd(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], out=self.Y, workspace=self.ws)
 
-    def backward(self, L):
+    def backward(self, L, phase=None):
         L.sr_linear_bwd(self.dY, self.W, self.A, self.q["dY_bwd"], self.q["W_bwd"], self.q["A_bwd"],
-                        out_dA=self.dA, out_dW=self.dW, workspace=self.ws)
+                        out_dA=self.dA, out_dW=self.dW, workspace=self.ws_bwd, phase=phase)
+
+    def forward_phase(self, L, phase):
+        L.sr_linear_fwd(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], out=self.Y, workspace=self.ws, phase=phase)
 
     def flops(self):
         return 6.0 * self.M * self.N * self.K
@@ -107,6 +112,40 @@ class Layer:
         """Every fp32 / bf16 tensor in once per quantizer pass, every result out once."""
         ew = self.W.element_size()
         return 4.0 * 3 * self.M * self.K + ew * 3.0 * self.N * self.K + 4.0 * 2 * self.M * self.N
+
+
+class TwoStreamStep:
+    """One step over several independent linears with the memory-bound half of the path (absmax, operand
+    quantizers) on one stream and the products on another: the quantizer and absmax kernels of the next
+    linears run on the CUs beside the product kernel of the current one (its two waves per SIMD leave
+    registers and LDS for one more wave), instead of each kernel waiting for the one before.  Every
+    launch of the single-stream step is made, with the same arguments; events carry the dependencies
+    (scales -> quantizers -> products), and both streams join the caller's stream at the end."""
+
+    def __init__(self, torch, L, layers):
+        self.torch, self.L, self.layers = torch, L, layers
+        self.mem, self.mat = torch.cuda.Stream(), torch.cuda.Stream()
+        self.ev = [(torch.cuda.Event(), torch.cuda.Event()) for _ in layers]
+
+    def __call__(self):
+        torch, L = self.torch, self.L
+        cur = torch.cuda.current_stream()
+        self.mem.wait_stream(cur)
+        self.mat.wait_stream(cur)
+        for ly, (ev_f, ev_b) in zip(self.layers, self.ev):
+            with torch.cuda.stream(self.mem):
+                ly.absmax.run()
+                ly.forward_phase(L, L.PHASE_QUANTIZE)
+                ev_f.record()
+                ly.backward(L, L.PHASE_QUANTIZE)
+                ev_b.record()
+            with torch.cuda.stream(self.mat):
+                self.mat.wait_event(ev_f)
+                ly.forward_phase(L, L.PHASE_PRODUCT)
+                self.mat.wait_event(ev_b)
+                ly.backward(L, L.PHASE_PRODUCT)
+        cur.wait_stream(self.mem)
+        cur.wait_stream(self.mat)
 
 
 def time_steps(torch, fn, steps, warmup):
@@ -522,10 +561,14 @@ def main():
 
     layers = llama_layers(L, synth, torch, TOKENS, synth.LLAMA_1B_LINEARS)
 
-    def step():
+    def step_one_stream():
         for ly in layers:
             ly.step(L)
+    # the step: every launch of the seven linears, the memory-bound half on one stream and the products
+    # on another (same launches, same arguments, same results as in a single stream)
+    step = TwoStreamStep(torch, L, layers)
     sec = time_steps(torch, step, args.steps, args.warmup)
+    sec_one = time_steps(torch, step_one_stream, args.steps, args.warmup)
     flops = sum(ly.flops() for ly in layers)
     io_bytes = sum(ly.min_hbm_bytes() for ly in layers)
     tflops = flops / sec / 1e12
@@ -560,6 +603,9 @@ def main():
         # at HBM peak, or the 8-bit MFMA peak, whichever is lower
         "composite_ceiling_TFLOP/s": round(min(MFMA_PEAK_TFLOPS["int8"],
                                                flops / (io_bytes / (HBM_PEAK_GBS * 1e9)) / 1e12), 1),
+        "streams": "2: absmax and operand quantizers on one stream, products on the other (events carry the "
+                   "dependencies); the kernels of the two streams share the CUs",
+        "single_stream": {"ms_per_step": round(sec_one * 1e3, 4), "TFLOP/s": round(flops / sec_one / 1e12, 1)},
         "per_shape": per_shape,
         "phases": phases,
     }

@@ -210,6 +210,25 @@ int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW
                   size_t N, size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* The two halves of sr_linear_fwd and of sr_linear_bwd as calls of their own, for callers that run the
+ * memory-bound half of one layer (rounding the operands into the workspace: SRQ_PHASE_QUANTIZE) beside
+ * the matrix half of another (the products from the workspace: SRQ_PHASE_PRODUCT) on two streams; the
+ * quantizer kernels fit into the registers and LDS the product kernels leave free on a CU.  Arguments as
+ * for the whole call, plus `phase`; the two calls of a pair take the same arguments and workspace, the
+ * caller orders them (same stream, or an event) and keeps the workspace untouched in between.
+ * SRQ_PHASE_BOTH is the whole call, except that sr_linear_fwd_phase always rounds into the workspace
+ * (never inside the product kernel).  The results equal those of the whole call bit for bit.  The
+ * product half does not read A, W or dY (the pointers are still checked).  Not available for the
+ * weight-only objective (SRQ_NONE: SRQ_ERR_UNSUPPORTED); an unknown phase is SRQ_ERR_FORMAT. */
+enum { SRQ_PHASE_QUANTIZE = 1, SRQ_PHASE_PRODUCT = 2, SRQ_PHASE_BOTH = 3 };
+int sr_linear_fwd_phase(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M,
+                        size_t N, size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd,
+                        void* workspace, size_t workspace_bytes, int phase, void* stream);
+int sr_linear_bwd_phase(float* dA, float* dW, const void* dY, int dtypedY, const void* W, int dtypeW,
+                        const void* A, int dtypeA, size_t M, size_t N, size_t K,
+                        const srq_quant* qdY_bwd, const srq_quant* qW_bwd, const srq_quant* qA_bwd,
+                        float beta, void* workspace, size_t workspace_bytes, int phase, void* stream);
+
 /* Alg. 1 with both quantizers inside the product kernel: every workgroup reads its tiles of A and
  * W in their source precision, applies Eq. 1 (the thresholds of an element are fixed by its
  * index, so the codes are the ones sr_quantize gives) and multiplies from LDS; no quantized

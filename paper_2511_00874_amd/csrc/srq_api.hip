@@ -193,8 +193,10 @@ int launch_backward_products(float* dA, float* dW, const uint8_t* dy_rm, const u
 //   out (P x Q) = Q(x)[P x R] . Q(z)[Q x R]^T,  x given as xr x xc (transposed if x_tr), same for z
 int run_linear(float* out, const void* x, int dtx, size_t xr, size_t xc, int x_tr, const srq_quant* qx,
                const void* z, int dtz, size_t zr, size_t zc, int z_tr, const srq_quant* qz, size_t P,
-               size_t Q, size_t R, float beta, void* workspace, size_t workspace_bytes, void* stream) {
+               size_t Q, size_t R, float beta, void* workspace, size_t workspace_bytes, void* stream,
+               int phase = SRQ_PHASE_BOTH) {
   if (!out) return SRQ_ERR_NULL;
+  if (phase < SRQ_PHASE_QUANTIZE || phase > SRQ_PHASE_BOTH) return SRQ_ERR_FORMAT;
   int st = check_operand(x, dtx, qx);
   if (st != SRQ_OK) return st;
   st = check_operand(z, dtz, qz);
@@ -213,8 +215,8 @@ int run_linear(float* out, const void* x, int dtx, size_t xr, size_t xc, int x_t
   // two) is the faster form -- measured 9.6 against 14.2 us on the 64 x 128 x 128 layer, but 27
   // against 14 us already at 128 x 128 x 768.  Integer pairs only: their results are the same bit
   // for bit in both forms.
-  if (!x_tr && !z_tr && beta == 0.0f && pp.pipe == PIPE_I8 && ((P + 63) / 64) * ((Q + 63) / 64) <= 4 && R <= 256 &&
-      !((qx->flags | qz->flags) & SRQ_FLAG_QUANTIZE_ONCE))
+  if (phase == SRQ_PHASE_BOTH && !x_tr && !z_tr && beta == 0.0f && pp.pipe == PIPE_I8 &&
+      ((P + 63) / 64) * ((Q + 63) / 64) <= 4 && R <= 256 && !((qx->flags | qz->flags) & SRQ_FLAG_QUANTIZE_ONCE))
     return launch_fused_fwd(out, x, make_args(qx, dtx, STORE_BYTE), z, make_args(qz, dtz, STORE_BYTE), P, Q, R, s) == hipSuccess
                ? SRQ_OK
                : SRQ_ERR_HIP;
@@ -226,7 +228,8 @@ int run_linear(float* out, const void* x, int dtx, size_t xr, size_t xc, int x_t
   jobs.njobs = 2;
   jobs.job[0] = make_job(qx, x, dtx, xr, xc, x_tr, store, xcodes, nullptr);
   jobs.job[1] = make_job(qz, z, dtz, zr, zc, z_tr, store, zcodes, nullptr);
-  if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  if ((phase & SRQ_PHASE_QUANTIZE) && launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  if (!(phase & SRQ_PHASE_PRODUCT)) return SRQ_OK;
   return launch_product(out, xcodes, qx, zcodes, qz, P, Q, R, pp, beta, gws, s);
 }
 
@@ -505,6 +508,14 @@ int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW
 }
 
 // Alg. 1 for callers that may not allocate: the workspace is the library's static device array.
+int sr_linear_fwd_phase(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
+                        size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd, void* workspace,
+                        size_t workspace_bytes, int phase, void* stream) {
+  if (is_none(qA_fwd)) return SRQ_ERR_UNSUPPORTED;
+  return run_linear(Y, A, dtypeA, M, K, 0, qA_fwd, W, dtypeW, N, K, 0, qW_fwd, M, N, K, 0.0f, workspace,
+                    workspace_bytes, stream, phase);
+}
+
 int sr_linear_fwd_fused(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
                         size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd, void* stream) {
   if (!Y) return SRQ_ERR_NULL;
@@ -562,7 +573,16 @@ int sr_linear_bwd_weight(float* dW, const void* dY, int dtypedY, const void* A, 
 int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void* W, int dtypeW, const void* A,
                   int dtypeA, size_t M, size_t N, size_t K, const srq_quant* qdY_bwd, const srq_quant* qW_bwd,
                   const srq_quant* qA_bwd, float beta, void* workspace, size_t workspace_bytes, void* stream) {
+  return sr_linear_bwd_phase(dA, dW, dY, dtypedY, W, dtypeW, A, dtypeA, M, N, K, qdY_bwd, qW_bwd, qA_bwd, beta,
+                             workspace, workspace_bytes, SRQ_PHASE_BOTH, stream);
+}
+
+int sr_linear_bwd_phase(float* dA, float* dW, const void* dY, int dtypedY, const void* W, int dtypeW, const void* A,
+                        int dtypeA, size_t M, size_t N, size_t K, const srq_quant* qdY_bwd, const srq_quant* qW_bwd,
+                        const srq_quant* qA_bwd, float beta, void* workspace, size_t workspace_bytes, int phase,
+                        void* stream) {
   if (!dA || !dW) return SRQ_ERR_NULL;
+  if (phase < SRQ_PHASE_QUANTIZE || phase > SRQ_PHASE_BOTH) return SRQ_ERR_FORMAT;
   int st = check_operand(dY, dtypedY, qdY_bwd);
   if (st != SRQ_OK) return st;
   st = check_operand(W, dtypeW, qW_bwd);
@@ -596,7 +616,8 @@ int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void*
   jobs.job[0] = make_job(qdY_bwd, dY, dtypedY, M, N, 1, store, dy_t, dy_rm);
   jobs.job[1] = make_job(qW_bwd, W, dtypeW, N, K, 1, store, w_t, nullptr);
   jobs.job[2] = make_job(qA_bwd, A, dtypeA, M, K, 1, store, a_t, nullptr);
-  if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  if ((phase & SRQ_PHASE_QUANTIZE) && launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  if (!(phase & SRQ_PHASE_PRODUCT)) return SRQ_OK;
   return launch_backward_products(dA, dW, dy_rm, w_t, dy_t, a_t, qdY_bwd, qW_bwd, qA_bwd, M, N, K, pd, pw, beta, gws_d,
                                   gws_w, s);
 }

@@ -510,7 +510,11 @@ __global__ __launch_bounds__(512) void gemm_nt_persist_kernel(GemmParams g, Slic
   };
 
   acc_t acc[TM][TN];
-  constexpr int PF = KSUB > 2 ? 2 : 1;
+    // fragments are read one sub-step ahead (two, as in gemm_nt_kernel, is no faster here and costs 24
+  // registers): at 219 VGPRs two waves of this kernel leave a SIMD 64 registers, enough for one wave
+  // of the quantizer or absmax kernels, so a memory-bound launch on another stream runs BESIDE this
+  // kernel on the same CUs instead of behind it
+  constexpr int PF = 1;
   auto compute = [&](uint32_t buf) {
     const uint8_t* stage = lds + buf * STAGE;
     raw_t xf[PF + 1][TM], zf[PF + 1][TN];

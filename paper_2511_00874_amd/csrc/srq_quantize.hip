@@ -281,7 +281,10 @@ __global__ __launch_bounds__(QBLOCK) void absmax_multi_kernel(AbsmaxBatch b) {
   }
 }
 
-constexpr int FINISH_BLOCK = 1024;
+// 256 threads (one wave per SIMD, 20 registers): small enough to start on a CU that a product kernel
+// occupies, when the scales are computed on a second stream beside the products of another layer (a
+// workgroup of 1024 threads waited there for a product launch to end, 200-700 us)
+constexpr int FINISH_BLOCK = 256;
 __global__ __launch_bounds__(FINISH_BLOCK) void absmax_multi_finish_kernel(AbsmaxBatch b) {
   __shared__ uint32_t part[FINISH_BLOCK / 64];
   const int t = blockIdx.x;  // one block per tensor

@@ -18,6 +18,7 @@ SR, RTN = 0, 1
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD, OP_FWD_STASH, OP_BWD_STASHED = 0, 1, 2, 3, 4, 5
 OP_FWD_WEIGHT_ONLY, OP_BWD_DATA_WEIGHT_ONLY = 6, 7
 FLAG_F8_PIPELINE, FLAG_COUNTER_DEV, FLAG_QUANTIZE_ONCE = 1, 2, 4
+PHASE_QUANTIZE, PHASE_PRODUCT, PHASE_BOTH = 1, 2, 3
 KIND_NAMES = {INT8: "int8", INT4: "int4", E4M3: "e4m3", E5M2: "e5m2", E4M2: "e4m2", E4M1: "e4m1", E4M0: "e4m0"}
 QMAX = {INT8: 127.0, INT4: 7.0, E4M3: 448.0, E5M2: 57344.0, E4M2: 448.0, E4M1: 384.0, E4M0: 256.0}
 
@@ -59,12 +60,15 @@ _lib.sr_linear_fwd.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _
 _lib.sr_linear_bwd_data.argtypes = _lib.sr_linear_fwd.argtypes
 _lib.sr_linear_fwd_static.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _vp]
 _lib.sr_linear_fwd_fused.argtypes = _lib.sr_linear_fwd_static.argtypes
+_lib.sr_linear_fwd_phase.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _vp, _sz, C.c_int, _vp]
 _lib.sr_linear_fwd_static_limit.argtypes = []
 _lib.sr_linear_fwd_static_limit.restype = _sz
 _lib.sr_linear_bwd_weight.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp,
                                       C.c_float, _vp, _sz, _vp]
 _lib.sr_linear_bwd.argtypes = [_vp, _vp, _vp, C.c_int, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp,
                                C.c_float, _vp, _sz, _vp]
+_lib.sr_linear_bwd_phase.argtypes = [_vp, _vp, _vp, C.c_int, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp,
+                                     C.c_float, _vp, _sz, C.c_int, _vp]
 _lib.sr_linear_workspace_bytes.argtypes = [C.c_int, _sz, _sz, _sz]
 _lib.sr_linear_workspace_bytes.restype = _sz
 _lib.sr_linear_stash_bytes.argtypes = [_sz, _sz, _sz]
@@ -74,7 +78,7 @@ _lib.sr_linear_bwd_stashed.argtypes = [_vp, _vp, _vp, C.c_int, _sz, _sz, _sz, _q
 _lib.sr_update_bf16.argtypes = [_vp, _vp, C.c_float, _sz, C.c_int, C.c_uint64, C.c_uint64, _vp]
 _lib.sr_status_string.argtypes = [C.c_int]
 _lib.sr_status_string.restype = C.c_char_p
-for _n in ("sr_linear_fwd_static", "sr_linear_fwd_fused", "sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_gemm_e5m2", "sr_linear_fwd", "sr_linear_bwd_data",
+for _n in ("sr_linear_fwd_static", "sr_linear_fwd_fused", "sr_linear_fwd_phase", "sr_linear_bwd_phase", "sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_gemm_e5m2", "sr_linear_fwd", "sr_linear_bwd_data",
            "sr_linear_bwd_weight", "sr_linear_bwd", "sr_update_bf16", "sr_linear_fwd_stash", "sr_linear_bwd_stashed"):
     getattr(_lib, _n).restype = C.c_int
 
@@ -82,7 +86,7 @@ EXPORTS = ["sr_absmax_scale", "sr_absmax_scales", "sr_absmax_workspace_bytes", "
            "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight", "sr_linear_bwd",
            "sr_linear_workspace_bytes", "sr_linear_stash_bytes", "sr_linear_fwd_stash", "sr_linear_bwd_stashed",
            "sr_update_bf16", "sr_status_string", "sr_linear_fwd_static", "sr_linear_fwd_static_limit",
-           "sr_linear_fwd_fused"]
+           "sr_linear_fwd_fused", "sr_linear_fwd_phase", "sr_linear_bwd_phase"]
 
 raw = _lib  # the C entry points themselves, for tests of the error paths
 
@@ -290,11 +294,16 @@ def _ws(op, M, N, K, workspace, device):
     return workspace
 
 
-def sr_linear_fwd(A, W, qA, qW, out=None, workspace=None):
+def sr_linear_fwd(A, W, qA, qW, out=None, workspace=None, phase=None):
     """Alg. 1: Y (M,N) = Q(A) Q(W)^T, A (M,K), W (N,K).  qA = Quant(NONE, 1.0): A as it is
-    (weight-only objective, Sec. 3.2)."""
+    (weight-only objective, Sec. 3.2).  phase = PHASE_QUANTIZE / PHASE_PRODUCT: one half of the call
+    (sr_linear_fwd_phase); `out` and `workspace` are then required."""
     M, K = A.shape
     N = W.shape[0]
+    if phase is not None:
+        _check(_lib.sr_linear_fwd_phase(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K, C.byref(qA.c()),
+                                        C.byref(qW.c()), _dev(workspace), workspace.numel(), phase, _stream()))
+        return out
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=A.device)
     ws = _ws(OP_FWD_WEIGHT_ONLY if qA.kind == NONE else OP_FWD, M, N, K, workspace, A.device)
@@ -349,10 +358,16 @@ def sr_linear_bwd_weight(dY, A, qdY, qA, out=None, beta=0.0, workspace=None):
     return out
 
 
-def sr_linear_bwd(dY, W, A, qdY, qW, qA, out_dA=None, out_dW=None, beta=0.0, workspace=None):
-    """Alg. 2 in one call: (dA, dW), with dY read and quantized once."""
+def sr_linear_bwd(dY, W, A, qdY, qW, qA, out_dA=None, out_dW=None, beta=0.0, workspace=None, phase=None):
+    """Alg. 2 in one call: (dA, dW), with dY read and quantized once.  phase = PHASE_QUANTIZE /
+    PHASE_PRODUCT: one half of the call (sr_linear_bwd_phase); outputs and workspace are then required."""
     M, N = dY.shape
     K = W.shape[1]
+    if phase is not None:
+        _check(_lib.sr_linear_bwd_phase(_dev(out_dA), _dev(out_dW), _dev(dY), _dtype(dY), _dev(W), _dtype(W), _dev(A),
+                                        _dtype(A), M, N, K, C.byref(qdY.c()), C.byref(qW.c()), C.byref(qA.c()), beta,
+                                        _dev(workspace), workspace.numel(), phase, _stream()))
+        return out_dA, out_dW
     if out_dA is None:
         out_dA = torch.empty((M, K), dtype=torch.float32, device=dY.device)
     if out_dW is None:

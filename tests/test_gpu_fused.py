@@ -121,3 +121,59 @@ def test_unsupported_pairs_are_refused():
         with pytest.raises(L.SrqError) as e:
             L.sr_linear_fwd_fused(A, W, L.Quant(kA, 1.0), L.Quant(kW, 1.0))
         assert e.value.status == -6
+
+
+# ---- the two halves of the linear calls as calls of their own (sr_linear_fwd_phase / sr_linear_bwd_phase) ----
+
+@pytest.mark.parametrize("kinds", [(L.INT8, L.INT8, L.INT4), (L.E5M2, L.E5M2, L.E5M2), (L.E4M3, L.E4M3, L.E5M2)])
+def test_phase_calls_equal_the_whole_call(kinds):
+    # quantize half on one stream, product half on another, ordered by an event: same results bit for bit
+    kA, kW, kdY = kinds
+    M, N, K = 528, 272, 400
+    A, W, dY = synth.single_layer(M, N, K, 31, std_dy=1e-3)
+    A, W, dY = to_dev(A), to_dev(W, True), to_dev(dY)
+    q = {}
+    off = 0
+    for name, t, kind in (("A_fwd", A, kA), ("W_fwd", W, kW), ("dY", dY, kdY), ("W_bwd", W, kW), ("A_bwd", A, kA)):
+        q[name] = L.Quant(kind, oracle.absmax_scale(host_src(t), kind), 8, off)
+        off += (t.numel() + 7) // 8
+    Y = L.sr_linear_fwd(A, W, q["A_fwd"], q["W_fwd"])
+    dA, dW = L.sr_linear_bwd(dY, W, A, q["dY"], q["W_bwd"], q["A_bwd"])
+    ws_f = torch.empty(L.sr_linear_workspace_bytes(L.OP_FWD, M, N, K), dtype=torch.uint8, device=A.device)
+    ws_b = torch.empty(L.sr_linear_workspace_bytes(L.OP_BWD, M, N, K), dtype=torch.uint8, device=A.device)
+    Y2, dA2, dW2 = torch.zeros_like(Y), torch.zeros_like(dA), torch.full_like(dW, 1.0)
+    mem, mat = torch.cuda.Stream(), torch.cuda.Stream()
+    ev_f, ev_b = torch.cuda.Event(), torch.cuda.Event()
+    cur = torch.cuda.current_stream()
+    mem.wait_stream(cur)
+    mat.wait_stream(cur)
+    with torch.cuda.stream(mem):
+        L.sr_linear_fwd(A, W, q["A_fwd"], q["W_fwd"], out=Y2, workspace=ws_f, phase=L.PHASE_QUANTIZE)
+        ev_f.record()
+        L.sr_linear_bwd(dY, W, A, q["dY"], q["W_bwd"], q["A_bwd"], out_dA=dA2, out_dW=dW2, workspace=ws_b,
+                        phase=L.PHASE_QUANTIZE)
+        ev_b.record()
+    with torch.cuda.stream(mat):
+        mat.wait_event(ev_f)
+        L.sr_linear_fwd(A, W, q["A_fwd"], q["W_fwd"], out=Y2, workspace=ws_f, phase=L.PHASE_PRODUCT)
+        mat.wait_event(ev_b)
+        L.sr_linear_bwd(dY, W, A, q["dY"], q["W_bwd"], q["A_bwd"], out_dA=dA2, out_dW=dW2, workspace=ws_b,
+                        phase=L.PHASE_PRODUCT)
+    cur.wait_stream(mem)
+    cur.wait_stream(mat)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2) and torch.equal(dA, dA2) and torch.equal(dW, dW2)
+    # the product half accumulates onto dW with beta = 1 as the whole call does
+    L.sr_linear_bwd(dY, W, A, q["dY"], q["W_bwd"], q["A_bwd"], out_dA=dA2, out_dW=dW2, beta=1.0, workspace=ws_b,
+                    phase=L.PHASE_PRODUCT)
+    assert torch.equal(dW2, dW + dW)
+    # PHASE_BOTH through the phase entry point; an unknown phase; the weight-only objective
+    Y3 = torch.zeros_like(Y)
+    L.sr_linear_fwd(A, W, q["A_fwd"], q["W_fwd"], out=Y3, workspace=ws_f, phase=L.PHASE_BOTH)
+    assert torch.equal(Y, Y3)
+    with pytest.raises(L.SrqError) as e:
+        L.sr_linear_fwd(A, W, q["A_fwd"], q["W_fwd"], out=Y3, workspace=ws_f, phase=7)
+    assert e.value.status == -3
+    with pytest.raises(L.SrqError) as e:
+        L.sr_linear_fwd(A, W, L.Quant(L.NONE, 1.0), q["W_fwd"], out=Y3, workspace=ws_f, phase=L.PHASE_PRODUCT)
+    assert e.value.status == -6
