@@ -507,16 +507,16 @@ def cpu_baseline():
         return flops / dt / 1e12, dt, flops
 
     threads = oracle.threads()
-    v_all, dt_all, fl_all = run(8192, 1 << 20)
+    v_all, dt_all, fl_all = run(16384, 1 << 21)
     oracle.set_threads(1)
-    v_one, dt_one, fl_one = run(512, 1 << 17)
+    v_one, dt_one, fl_one = run(1024, 1 << 18)
     oracle.set_threads(threads)
     return {"value": round(v_all, 6), "unit": "TFLOP/s", "cores": threads, "kind": "oracle", "cpu_model": cpu_model(),
-            "sample": f"2048x2048 linear (bf16 W, int8 quantizers, int4 dY) at 8192 tokens: 5 absmax + the 6 "
-                      f"quantizations of the full tensors, then 3 x {1 << 20} sampled entries of Y/dA/dW; "
+            "sample": f"2048x2048 linear (bf16 W, int8 quantizers, int4 dY) at 16384 tokens: 5 absmax + the 6 "
+                      f"quantizations of the full tensors, then 3 x {1 << 21} sampled entries of Y/dA/dW; "
                       f"{fl_all / 1e9:.1f} GFLOP of products in {dt_all:.1f} s wall",
             "single_thread": {"value": round(v_one, 6), "unit": "TFLOP/s", "cores": 1,
-                              "sample": f"the same at 512 tokens with 3 x {1 << 17} sampled entries; "
+                              "sample": f"the same at 1024 tokens with 3 x {1 << 18} sampled entries; "
                                         f"{fl_one / 1e9:.1f} GFLOP of products in {dt_one:.1f} s wall"}}
 
 
