@@ -50,7 +50,8 @@ def parse():
 class Layer:
     """One linear's tensors, scales, quantizers, outputs and workspaces, all preallocated."""
 
-    def __init__(self, L, synth, torch, name, M, N, K, seed, f8_flag=0, kinds=None, w_bf16=False, counters_dev=False):
+    def __init__(self, L, synth, torch, name, M, N, K, seed, f8_flag=0, kinds=None, w_bf16=False, counters_dev=False,
+                 stash=False):
         dev = "cuda:0"
         self.name, self.M, self.N, self.K = name, M, N, K
         self.A = synth.gaussian_torch((M, K), 1.0, seed, dev)
@@ -82,8 +83,12 @@ class Layer:
         self.dW = torch.empty((N, K), dtype=torch.float32, device=dev)
         # forward and backward operands in workspaces of their own: the backward operands of a layer can
         # then be rounded while its forward product still reads the forward ones
-        self.ws = torch.empty(L.sr_linear_workspace_bytes(L.OP_FWD, M, N, K), dtype=torch.uint8, device=dev)
-        self.ws_bwd = torch.empty(L.sr_linear_workspace_bytes(L.OP_BWD, M, N, K), dtype=torch.uint8, device=dev)
+        # `stash`: the forward pass also rounds A and W with the backward quantizers (one read of each feeds
+        # both of its quantizers) and keeps those codes for the backward pass, which then reads only dY
+        self.stash = torch.empty(L.sr_linear_stash_bytes(M, N, K), dtype=torch.uint8, device=dev) if stash else None
+        op_f, op_b = (L.OP_FWD_STASH, L.OP_BWD_STASHED) if stash else (L.OP_FWD, L.OP_BWD)
+        self.ws = torch.empty(L.sr_linear_workspace_bytes(op_f, M, N, K), dtype=torch.uint8, device=dev)
+        self.ws_bwd = torch.empty(L.sr_linear_workspace_bytes(op_b, M, N, K), dtype=torch.uint8, device=dev)
         self.absmax = L.AbsmaxBatch([(t, kind, s) for t, kind, s in self.src_of.values()])
 
     def step(self, L):
@@ -96,22 +101,37 @@ class Layer:
             self.counters.add_(self.advance)
 
     def forward(self, L):
+        if self.stash is not None:
+            return self.forward_phase(L, L.PHASE_BOTH)
         L.sr_linear_fwd(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], out=self.Y, workspace=self.ws)
 
     def backward(self, L, phase=None):
-        L.sr_linear_bwd(self.dY, self.W, self.A, self.q["dY_bwd"], self.q["W_bwd"], self.q["A_bwd"],
-                        out_dA=self.dA, out_dW=self.dW, workspace=self.ws_bwd, phase=phase)
+        q = self.q
+        if self.stash is not None:
+            L.sr_linear_bwd_stashed(self.dY, self.stash, self.K, q["dY_bwd"], q["W_bwd"], q["A_bwd"], out_dA=self.dA,
+                                    out_dW=self.dW, workspace=self.ws_bwd, phase=phase or L.PHASE_BOTH)
+        else:
+            L.sr_linear_bwd(self.dY, self.W, self.A, q["dY_bwd"], q["W_bwd"], q["A_bwd"],
+                            out_dA=self.dA, out_dW=self.dW, workspace=self.ws_bwd, phase=phase)
 
     def forward_phase(self, L, phase):
-        L.sr_linear_fwd(self.A, self.W, self.q["A_fwd"], self.q["W_fwd"], out=self.Y, workspace=self.ws, phase=phase)
+        q = self.q
+        if self.stash is not None:
+            L.sr_linear_fwd_stash(self.A, self.W, q["A_fwd"], q["W_fwd"], q["A_bwd"], q["W_bwd"], stash=self.stash,
+                                  out=self.Y, workspace=self.ws, phase=phase)
+        else:
+            L.sr_linear_fwd(self.A, self.W, q["A_fwd"], q["W_fwd"], out=self.Y, workspace=self.ws, phase=phase)
 
     def flops(self):
         return 6.0 * self.M * self.N * self.K
 
     def min_hbm_bytes(self):
-        """Every fp32 / bf16 tensor in once per quantizer pass, every result out once."""
+        """Every fp32 / bf16 tensor in once per pass over it (absmax, forward quantizers, backward quantizers;
+        with the stash the forward pass over A and W serves their backward quantizers too), every result out once."""
         ew = self.W.element_size()
-        return 4.0 * 3 * self.M * self.K + ew * 3.0 * self.N * self.K + 4.0 * 2 * self.M * self.N
+        passes = 2.0 if self.stash is not None else 3.0
+        return (4.0 * passes * self.M * self.K + ew * passes * self.N * self.K + 4.0 * 2 * self.M * self.N
+                + 4.0 * (self.M * self.N + self.M * self.K + self.N * self.K))
 
 
 class TwoStreamStep:
@@ -188,7 +208,7 @@ LLAMA_KINDS = ("A_fwd", "W_fwd", "A_bwd", "W_bwd")
 def llama_layers(L, synth, torch, T, shapes, seed0=7):
     kinds = {k: L.INT8 for k in LLAMA_KINDS}
     kinds["dY_bwd"] = L.INT4
-    return [Layer(L, synth, torch, nm, T, N, K, seed0 + 10 * i, kinds=kinds, w_bf16=True)
+    return [Layer(L, synth, torch, nm, T, N, K, seed0 + 10 * i, kinds=kinds, w_bf16=True, stash=True)
             for i, (nm, N, K) in enumerate(shapes)]
 
 
@@ -316,7 +336,7 @@ def gpt2_mlp(L, synth, torch, steps, warmup):
     res["flop_per_step"], res["min_hbm_bytes_per_step"] = flops, io_bytes
     res["composite_ceiling_TFLOP/s"] = round(flops / (io_bytes / (HBM_PEAK_GBS * 1e9)) / 1e12, 1)
     for label, flag in (("exact", 0), ("f8_pipeline", L.FLAG_F8_PIPELINE)):
-        layers = [Layer(L, synth, torch, nm, GPT2_TOKENS, N, K, 100 + 10 * i, flag) for i, (nm, N, K) in enumerate(shapes)]
+        layers = [Layer(L, synth, torch, nm, GPT2_TOKENS, N, K, 100 + 10 * i, flag, stash=True) for i, (nm, N, K) in enumerate(shapes)]
 
         def step():
             for ly in layers:
@@ -331,7 +351,7 @@ def gpt2_mlp(L, synth, torch, steps, warmup):
             sec_gs = time_steps(torch, step_given_scales, steps, warmup)
             res["scales_given"] = {"ms_per_step": round(sec_gs * 1e3, 4), "TFLOP/s": round(flops / sec_gs / 1e12, 1)}
             # the same step recorded once and replayed: one graph launch per step instead of 14
-            glayers = [Layer(L, synth, torch, nm, GPT2_TOKENS, N, K, 100 + 10 * i, flag, counters_dev=True)
+            glayers = [Layer(L, synth, torch, nm, GPT2_TOKENS, N, K, 100 + 10 * i, flag, counters_dev=True, stash=True)
                        for i, (nm, N, K) in enumerate(shapes)]
 
             def gstep():

@@ -316,6 +316,17 @@ int sr_linear_bwd_stashed(float* dA, float* dW, const void* dY, int dtypedY, siz
                           const srq_quant* qdY_bwd, const srq_quant* qW_bwd, const srq_quant* qA_bwd,
                           const void* stash, size_t stash_bytes, float beta, void* workspace,
                           size_t workspace_bytes, void* stream);
+/* The same two calls in halves (`phase` as for sr_linear_fwd_phase: the quantizer launch into the
+ * workspace and the stash, or the products from them, or both); the two calls of a pair take the
+ * same arguments, workspace and stash, and the caller orders them. */
+int sr_linear_fwd_stash_phase(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
+                              size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd,
+                              const srq_quant* qA_bwd, const srq_quant* qW_bwd, void* stash, size_t stash_bytes,
+                              void* workspace, size_t workspace_bytes, int phase, void* stream);
+int sr_linear_bwd_stashed_phase(float* dA, float* dW, const void* dY, int dtypedY, size_t M, size_t N, size_t K,
+                                const srq_quant* qdY_bwd, const srq_quant* qW_bwd, const srq_quant* qA_bwd,
+                                const void* stash, size_t stash_bytes, float beta, void* workspace,
+                                size_t workspace_bytes, int phase, void* stream);
 
 /* Weight update of Eq. 10 with the weights stored in bfloat16, in place:
  *     w[i] <- Q(w[i] - eta * g[i]),   i in [0, n)

@@ -507,7 +507,7 @@ int sr_linear_fwd(float* Y, const void* A, int dtypeA, const void* W, int dtypeW
                     workspace_bytes, stream);
 }
 
-// Alg. 1 for callers that may not allocate: the workspace is the library's static device array.
+// Alg. 1 in two halves: the quantizer launch, the product launch, or both.
 int sr_linear_fwd_phase(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
                         size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd, void* workspace,
                         size_t workspace_bytes, int phase, void* stream) {
@@ -535,6 +535,7 @@ int sr_linear_fwd_fused(float* Y, const void* A, int dtypeA, const void* W, int 
              : SRQ_ERR_HIP;
 }
 
+// Alg. 1 for callers that may not allocate: the workspace is the library's static device array.
 size_t sr_linear_fwd_static_limit(void) { return SRQ_STATIC_SCRATCH_BYTES; }
 
 int sr_linear_fwd_static(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
@@ -647,7 +648,16 @@ int sr_linear_fwd_stash(float* Y, const void* A, int dtypeA, const void* W, int 
                         size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd, const srq_quant* qA_bwd,
                         const srq_quant* qW_bwd, void* stash, size_t stash_bytes, void* workspace,
                         size_t workspace_bytes, void* stream) {
+  return sr_linear_fwd_stash_phase(Y, A, dtypeA, W, dtypeW, M, N, K, qA_fwd, qW_fwd, qA_bwd, qW_bwd, stash, stash_bytes,
+                                   workspace, workspace_bytes, SRQ_PHASE_BOTH, stream);
+}
+
+int sr_linear_fwd_stash_phase(float* Y, const void* A, int dtypeA, const void* W, int dtypeW, size_t M, size_t N,
+                              size_t K, const srq_quant* qA_fwd, const srq_quant* qW_fwd, const srq_quant* qA_bwd,
+                              const srq_quant* qW_bwd, void* stash, size_t stash_bytes, void* workspace,
+                              size_t workspace_bytes, int phase, void* stream) {
   if (!Y) return SRQ_ERR_NULL;
+  if (phase < SRQ_PHASE_QUANTIZE || phase > SRQ_PHASE_BOTH) return SRQ_ERR_FORMAT;
   int st = check_operand(A, dtypeA, qA_fwd);
   if (st != SRQ_OK) return st;
   st = check_operand(W, dtypeW, qW_fwd);
@@ -678,7 +688,8 @@ int sr_linear_fwd_stash(float* Y, const void* A, int dtypeA, const void* W, int 
   jobs.njobs = 2;
   jobs.job[0] = make_dual_job(qA_bwd, qA_fwd, A, dtypeA, M, K, store, a_t, a_codes);
   jobs.job[1] = make_dual_job(qW_bwd, qW_fwd, W, dtypeW, N, K, store, w_t, w_codes);
-  if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  if ((phase & SRQ_PHASE_QUANTIZE) && launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  if (!(phase & SRQ_PHASE_PRODUCT)) return SRQ_OK;
   return launch_product(Y, a_codes, qA_fwd, w_codes, qW_fwd, M, N, K, pf, 0.0f, gws, s);
 }
 
@@ -687,7 +698,16 @@ int sr_linear_bwd_stashed(float* dA, float* dW, const void* dY, int dtypedY, siz
                           const srq_quant* qdY_bwd, const srq_quant* qW_bwd, const srq_quant* qA_bwd,
                           const void* stash, size_t stash_bytes, float beta, void* workspace,
                           size_t workspace_bytes, void* stream) {
+  return sr_linear_bwd_stashed_phase(dA, dW, dY, dtypedY, M, N, K, qdY_bwd, qW_bwd, qA_bwd, stash, stash_bytes, beta,
+                                     workspace, workspace_bytes, SRQ_PHASE_BOTH, stream);
+}
+
+int sr_linear_bwd_stashed_phase(float* dA, float* dW, const void* dY, int dtypedY, size_t M, size_t N, size_t K,
+                                const srq_quant* qdY_bwd, const srq_quant* qW_bwd, const srq_quant* qA_bwd,
+                                const void* stash, size_t stash_bytes, float beta, void* workspace,
+                                size_t workspace_bytes, int phase, void* stream) {
   if (!dA || !dW) return SRQ_ERR_NULL;
+  if (phase < SRQ_PHASE_QUANTIZE || phase > SRQ_PHASE_BOTH) return SRQ_ERR_FORMAT;
   int st = check_operand(dY, dtypedY, qdY_bwd);
   if (st != SRQ_OK) return st;
   if ((st = check_quant(qA_bwd)) != SRQ_OK || (st = check_quant(qW_bwd)) != SRQ_OK) return st;
@@ -719,7 +739,8 @@ int sr_linear_bwd_stashed(float* dA, float* dW, const void* dY, int dtypedY, siz
   QuantJobs jobs;
   jobs.njobs = 1;
   jobs.job[0] = make_job(qdY_bwd, dY, dtypedY, M, N, 1, store, dy_t, dy_rm);
-  if (launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  if ((phase & SRQ_PHASE_QUANTIZE) && launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
+  if (!(phase & SRQ_PHASE_PRODUCT)) return SRQ_OK;
   return launch_backward_products(dA, dW, dy_rm, w_t, dy_t, a_t, qdY_bwd, qW_bwd, qA_bwd, M, N, K, pd, pw, beta, gws_d,
                                   gws_w, s);
 }

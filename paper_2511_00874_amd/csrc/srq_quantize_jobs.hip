@@ -15,6 +15,7 @@ namespace {
 
 constexpr int QBLOCK = 256;
 constexpr int TR = 128, TC = 64;        // transposing tile: TR source rows x TC source columns
+constexpr int BAND_GROUP = 16;          // row bands whose tiles are walked together (tile order)
 constexpr int FLAT_GROUPS_PER_BLOCK = QBLOCK * 4;  // sixteen 512-element chunks: four per wave (measured best of 1, 2, 4, 8)
 
 template <int KIND, bool AS_BF16>
@@ -86,8 +87,14 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
   const uint64_t ctr = first_block(j.counter_offset, j.counter_dev);
   const uint64_t ctr2 = j.out2 && j.kind2 ? first_block(j.counter_offset2, j.counter_dev2) : 0ull;
   const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
-  const uint32_t tiles_x = (j.cols + TC - 1) / TC;
-  const uint32_t r0 = (local / tiles_x) * TR, c0 = (local % tiles_x) * TC;
+  // Tile order: bands of TR source rows in groups of BAND_GROUP; inside a group the band index runs
+  // fastest, then the column tile.  Workgroups that run together then write BAND_GROUP * TR
+  // consecutive elements of every transposed row between them, and still read each source row in
+  // neighbouring pieces.
+  const uint32_t tiles_x = (j.cols + TC - 1) / TC, tiles_y = (j.rows + TR - 1) / TR;
+  const uint32_t group = local / (BAND_GROUP * tiles_x), within = local % (BAND_GROUP * tiles_x);
+  const uint32_t bands = min((uint32_t)BAND_GROUP, tiles_y - group * BAND_GROUP);
+  const uint32_t r0 = (group * BAND_GROUP + within % bands) * TR, c0 = (within / bands) * TC;
   const uint32_t rows = j.rows, cols = j.cols;
   const size_t n = (size_t)rows * cols;
   if (j.dtype == SRQ_F32) {

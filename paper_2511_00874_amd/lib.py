@@ -75,18 +75,24 @@ _lib.sr_linear_stash_bytes.argtypes = [_sz, _sz, _sz]
 _lib.sr_linear_stash_bytes.restype = _sz
 _lib.sr_linear_fwd_stash.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp, _qp, _vp, _sz, _vp, _sz, _vp]
 _lib.sr_linear_bwd_stashed.argtypes = [_vp, _vp, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp, _vp, _sz, C.c_float, _vp, _sz, _vp]
+_lib.sr_linear_fwd_stash_phase.argtypes = [_vp, _vp, C.c_int, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp, _qp, _vp, _sz, _vp, _sz,
+                                           C.c_int, _vp]
+_lib.sr_linear_bwd_stashed_phase.argtypes = [_vp, _vp, _vp, C.c_int, _sz, _sz, _sz, _qp, _qp, _qp, _vp, _sz, C.c_float, _vp, _sz,
+                                             C.c_int, _vp]
 _lib.sr_update_bf16.argtypes = [_vp, _vp, C.c_float, _sz, C.c_int, C.c_uint64, C.c_uint64, _vp]
 _lib.sr_status_string.argtypes = [C.c_int]
 _lib.sr_status_string.restype = C.c_char_p
 for _n in ("sr_linear_fwd_static", "sr_linear_fwd_fused", "sr_linear_fwd_phase", "sr_linear_bwd_phase", "sr_absmax_scale", "sr_absmax_scales", "sr_quantize", "sr_gemm_codes", "sr_gemm_bf16", "sr_gemm_e5m2", "sr_linear_fwd", "sr_linear_bwd_data",
-           "sr_linear_bwd_weight", "sr_linear_bwd", "sr_update_bf16", "sr_linear_fwd_stash", "sr_linear_bwd_stashed"):
+           "sr_linear_bwd_weight", "sr_linear_bwd", "sr_update_bf16", "sr_linear_fwd_stash", "sr_linear_bwd_stashed",
+           "sr_linear_fwd_stash_phase", "sr_linear_bwd_stashed_phase"):
     getattr(_lib, _n).restype = C.c_int
 
 EXPORTS = ["sr_absmax_scale", "sr_absmax_scales", "sr_absmax_workspace_bytes", "sr_quantize", "sr_gemm_codes", "sr_gemm_workspace_bytes", "sr_gemm_bf16", "sr_gemm_bf16_workspace_bytes", "sr_gemm_e5m2", "sr_gemm_e5m2_workspace_bytes",
            "sr_linear_fwd", "sr_linear_bwd_data", "sr_linear_bwd_weight", "sr_linear_bwd",
            "sr_linear_workspace_bytes", "sr_linear_stash_bytes", "sr_linear_fwd_stash", "sr_linear_bwd_stashed",
            "sr_update_bf16", "sr_status_string", "sr_linear_fwd_static", "sr_linear_fwd_static_limit",
-           "sr_linear_fwd_fused", "sr_linear_fwd_phase", "sr_linear_bwd_phase"]
+           "sr_linear_fwd_fused", "sr_linear_fwd_phase", "sr_linear_bwd_phase", "sr_linear_fwd_stash_phase",
+           "sr_linear_bwd_stashed_phase"]
 
 raw = _lib  # the C entry points themselves, for tests of the error paths
 
@@ -185,8 +191,9 @@ def sr_linear_stash_bytes(M, N, K):
     return _lib.sr_linear_stash_bytes(M, N, K)
 
 
-def sr_linear_fwd_stash(A, W, qA, qW, qA_bwd, qW_bwd, stash=None, out=None, workspace=None):
-    """Alg. 1 that also saves Q(A; qA_bwd)^T and Q(W; qW_bwd)^T in code form: returns (Y, stash)."""
+def sr_linear_fwd_stash(A, W, qA, qW, qA_bwd, qW_bwd, stash=None, out=None, workspace=None, phase=PHASE_BOTH):
+    """Alg. 1 that also saves Q(A; qA_bwd)^T and Q(W; qW_bwd)^T in code form: returns (Y, stash).
+    `phase`: the quantizer launch, the product, or both (the halves take the same out, stash, workspace)."""
     M, K = A.shape
     N = W.shape[0]
     if out is None:
@@ -194,23 +201,24 @@ def sr_linear_fwd_stash(A, W, qA, qW, qA_bwd, qW_bwd, stash=None, out=None, work
     if stash is None:
         stash = torch.empty(sr_linear_stash_bytes(M, N, K), dtype=torch.uint8, device=A.device)
     ws = _ws(OP_FWD_STASH, M, N, K, workspace, A.device)
-    _check(_lib.sr_linear_fwd_stash(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K, C.byref(qA.c()),
-                                    C.byref(qW.c()), C.byref(qA_bwd.c()), C.byref(qW_bwd.c()), _dev(stash),
-                                    stash.numel(), _dev(ws), ws.numel(), _stream()))
+    _check(_lib.sr_linear_fwd_stash_phase(_dev(out), _dev(A), _dtype(A), _dev(W), _dtype(W), M, N, K, C.byref(qA.c()),
+                                          C.byref(qW.c()), C.byref(qA_bwd.c()), C.byref(qW_bwd.c()), _dev(stash),
+                                          stash.numel(), _dev(ws), ws.numel(), phase, _stream()))
     return out, stash
 
 
-def sr_linear_bwd_stashed(dY, stash, K, qdY, qW, qA, out_dA=None, out_dW=None, beta=0.0, workspace=None):
-    """Alg. 2 from the stash of sr_linear_fwd_stash: (dA, dW); only dY is read."""
+def sr_linear_bwd_stashed(dY, stash, K, qdY, qW, qA, out_dA=None, out_dW=None, beta=0.0, workspace=None,
+                          phase=PHASE_BOTH):
+    """Alg. 2 from the stash of sr_linear_fwd_stash: (dA, dW); only dY is read.  `phase` as above."""
     M, N = dY.shape
     if out_dA is None:
         out_dA = torch.empty((M, K), dtype=torch.float32, device=dY.device)
     if out_dW is None:
         out_dW = torch.empty((N, K), dtype=torch.float32, device=dY.device)
     ws = _ws(OP_BWD_STASHED, M, N, K, workspace, dY.device)
-    _check(_lib.sr_linear_bwd_stashed(_dev(out_dA), _dev(out_dW), _dev(dY), _dtype(dY), M, N, K, C.byref(qdY.c()),
-                                      C.byref(qW.c()), C.byref(qA.c()), _dev(stash), stash.numel(), beta, _dev(ws),
-                                      ws.numel(), _stream()))
+    _check(_lib.sr_linear_bwd_stashed_phase(_dev(out_dA), _dev(out_dW), _dev(dY), _dtype(dY), M, N, K, C.byref(qdY.c()),
+                                            C.byref(qW.c()), C.byref(qA.c()), _dev(stash), stash.numel(), beta, _dev(ws),
+                                            ws.numel(), phase, _stream()))
     return out_dA, out_dW
 
 

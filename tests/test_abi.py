@@ -113,6 +113,15 @@ def test_linear_argument_checks(lib):
     assert r.sr_linear_fwd_stash(*args, 64, 128, 128, C.byref(q8), C.byref(q8), C.byref(q52), C.byref(q52), None, 0, buf, ws,
                                  None) == -5
     assert lib.sr_linear_stash_bytes(64, 128, 128) >= 2 * 128 * (64 + 128)
+    # the same pair in halves: an unknown phase is refused before anything else is looked at
+    assert r.sr_linear_fwd_stash_phase(*args, 64, 128, 128, C.byref(q8), C.byref(q8), C.byref(q52), C.byref(q52), buf, ws, buf,
+                                       ws, 4, None) == -3
+    assert r.sr_linear_fwd_stash_phase(*args, 64, 128, 128, C.byref(qf), C.byref(qf), C.byref(q52), C.byref(q52), buf, ws, buf,
+                                       ws, 1, None) == -6
+    assert r.sr_linear_bwd_stashed_phase(buf, buf, buf, 0, 64, 128, 128, C.byref(q52), C.byref(q52), C.byref(q52), buf, ws,
+                                         0.0, buf, ws, 0, None) == -3
+    assert r.sr_linear_bwd_stashed_phase(buf, buf, buf, 0, 64, 128, 128, C.byref(q52), C.byref(q52), C.byref(q52), None, 0,
+                                         0.0, buf, 1 << 30, 2, None) == -5
     # the identity quantizer: row operand of the forward and input-gradient products only
     q0 = _q(lib, 0)
     assert r.sr_linear_fwd(*args, 64, 128, 128, C.byref(q8), C.byref(q0), buf, ws, None) == -6

@@ -177,3 +177,53 @@ def test_phase_calls_equal_the_whole_call(kinds):
     with pytest.raises(L.SrqError) as e:
         L.sr_linear_fwd(A, W, L.Quant(L.NONE, 1.0), q["W_fwd"], out=Y3, workspace=ws_f, phase=L.PHASE_PRODUCT)
     assert e.value.status == -6
+
+
+@pytest.mark.parametrize("kinds", [(L.INT8, L.INT4), (L.E5M2, L.E5M2), (L.E4M3, L.E5M2)])
+def test_phase_calls_with_the_stash_equal_the_whole_calls(kinds):
+    # forward that also rounds the backward operands of A and W (read once), backward from that stash: in
+    # halves on two streams, against sr_linear_fwd / sr_linear_bwd with the same five quantizers
+    kb, kdY = kinds
+    M, N, K = 528, 272, 400
+    A, W, dY = synth.single_layer(M, N, K, 37, std_dy=1e-3)
+    A, W, dY = to_dev(A), to_dev(W, True), to_dev(dY)
+    q, off = {}, 0
+    for name, t, kind in (("A_fwd", A, L.INT8), ("W_fwd", W, L.INT8), ("dY", dY, kdY), ("W_bwd", W, kb), ("A_bwd", A, kb)):
+        q[name] = L.Quant(kind, oracle.absmax_scale(host_src(t), kind), 12, off)
+        off += (t.numel() + 7) // 8
+    Y = L.sr_linear_fwd(A, W, q["A_fwd"], q["W_fwd"])
+    dA, dW = L.sr_linear_bwd(dY, W, A, q["dY"], q["W_bwd"], q["A_bwd"])
+    dev = A.device
+    stash = torch.empty(L.sr_linear_stash_bytes(M, N, K), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(L.sr_linear_workspace_bytes(L.OP_FWD_STASH, M, N, K), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(L.sr_linear_workspace_bytes(L.OP_BWD_STASHED, M, N, K), dtype=torch.uint8, device=dev)
+    Y2, dA2, dW2 = torch.zeros_like(Y), torch.zeros_like(dA), torch.full_like(dW, 1.0)
+    fwd = dict(stash=stash, out=Y2, workspace=ws_f)
+    bwd = dict(out_dA=dA2, out_dW=dW2, workspace=ws_b)
+    mem, mat = torch.cuda.Stream(), torch.cuda.Stream()
+    ev_f, ev_b = torch.cuda.Event(), torch.cuda.Event()
+    cur = torch.cuda.current_stream()
+    mem.wait_stream(cur)
+    mat.wait_stream(cur)
+    with torch.cuda.stream(mem):
+        L.sr_linear_fwd_stash(A, W, q["A_fwd"], q["W_fwd"], q["A_bwd"], q["W_bwd"], phase=L.PHASE_QUANTIZE, **fwd)
+        ev_f.record()
+        L.sr_linear_bwd_stashed(dY, stash, K, q["dY"], q["W_bwd"], q["A_bwd"], phase=L.PHASE_QUANTIZE, **bwd)
+        ev_b.record()
+    with torch.cuda.stream(mat):
+        mat.wait_event(ev_f)
+        L.sr_linear_fwd_stash(A, W, q["A_fwd"], q["W_fwd"], q["A_bwd"], q["W_bwd"], phase=L.PHASE_PRODUCT, **fwd)
+        mat.wait_event(ev_b)
+        L.sr_linear_bwd_stashed(dY, stash, K, q["dY"], q["W_bwd"], q["A_bwd"], phase=L.PHASE_PRODUCT, **bwd)
+    cur.wait_stream(mem)
+    cur.wait_stream(mat)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2) and torch.equal(dA, dA2) and torch.equal(dW, dW2)
+    L.sr_linear_bwd_stashed(dY, stash, K, q["dY"], q["W_bwd"], q["A_bwd"], beta=1.0, phase=L.PHASE_PRODUCT, **bwd)
+    assert torch.equal(dW2, dW + dW)
+    with pytest.raises(L.SrqError) as e:
+        L.sr_linear_bwd_stashed(dY, stash, K, q["dY"], q["W_bwd"], q["A_bwd"], phase=0, **bwd)
+    assert e.value.status == -3
+    with pytest.raises(L.SrqError) as e:
+        L.sr_linear_fwd_stash(A, W, q["A_fwd"], q["W_fwd"], q["A_bwd"], q["W_bwd"], phase=4, **fwd)
+    assert e.value.status == -3
