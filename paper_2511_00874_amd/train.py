@@ -19,8 +19,9 @@ NOQ = L.Quant(L.NONE, 1.0)  # the identity quantizer of the weight-only objectiv
 
 class SRLinearFn(torch.autograd.Function):
     """Everything the backward pass of ONE forward call needs travels on the autograd context:
-    the saved activation, the stream positions drawn for the backward quantizers of A and W, the
-    scales found for them and (objectives that share one quantized weight copy between the
+    the saved activation -- as the codes of its backward quantizer when the forward pass can write
+    them (the stash of sr_linear_fwd_stash: integer forward formats), else in binary32 -- the
+    stream positions drawn for the backward quantizers of A and W, the scales found for them and (objectives that share one quantized weight copy between the
     passes) the weight quantizer itself.  A second forward of the same layer before the first
     backward therefore cannot disturb the first one's gradients."""
 
@@ -29,13 +30,14 @@ class SRLinearFn(torch.autograd.Function):
         ctx.layer = layer
         ctx.shape = x.shape
         a = x.reshape(-1, x.shape[-1]).contiguous().float()
-        ctx.save_for_backward(a)
         y, ctx.saved = layer._forward(a)
+        if "stash" not in ctx.saved:  # the backward pass quantizes (or multiplies) the activation itself
+            ctx.save_for_backward(a)
         return y.reshape(*x.shape[:-1], layer.out_features)
 
     @staticmethod
     def backward(ctx, dy):
-        (a,) = ctx.saved_tensors
+        a = ctx.saved_tensors[0] if ctx.saved_tensors else None
         layer = ctx.layer
         da = layer._backward(dy.reshape(-1, layer.out_features).contiguous().float(), a, ctx.saved)
         return da.reshape(ctx.shape), None
@@ -152,10 +154,21 @@ class SRLinear(torch.nn.Module):
         self.position = pos_a + 2 * a_blocks + w_blocks
         y = torch.empty((M, N), dtype=torch.float32, device=a.device)
         qw = self._q("W_fwd", sc[1:2], pos_w)
+        # integer forward formats: the same pass over A and W also writes the codes of their backward
+        # quantizers (one stash per chunk of rows), and the activation itself need not be kept
+        stash = self.kinds["A_fwd"] in (L.INT8, L.INT4)
+        if stash:
+            saved["stash"] = []
         for r0 in range(0, M, MAX_ROWS):
             r1 = min(M, r0 + MAX_ROWS)
-            L.sr_linear_fwd(a[r0:r1], w, self._q("A_fwd", sc[0:1], pos_a + (r0 * K) // 8), qw, out=y[r0:r1],
-                            workspace=self._workspace(L.OP_FWD, r1 - r0))
+            qa = self._q("A_fwd", sc[0:1], pos_a + (r0 * K) // 8)
+            if stash:
+                qa_bwd = self._q("A_bwd", saved["sA"], saved["pos_a"] + (r0 * K) // 8)
+                _, st = L.sr_linear_fwd_stash(a[r0:r1], w, qa, qw, qa_bwd, saved["qw"], out=y[r0:r1],
+                                              workspace=self._workspace(L.OP_FWD_STASH, r1 - r0))
+                saved["stash"].append(st)
+            else:
+                L.sr_linear_fwd(a[r0:r1], w, qa, qw, out=y[r0:r1], workspace=self._workspace(L.OP_FWD, r1 - r0))
         return y, saved
 
     def _backward(self, dy, a, saved):
@@ -171,12 +184,17 @@ class SRLinear(torch.nn.Module):
         da = torch.empty((M, K), dtype=torch.float32, device=dy.device)
         pos_dy = self.position
         self.position += (M * N + 7) // 8
-        for r0 in range(0, M, MAX_ROWS):
+        for i, r0 in enumerate(range(0, M, MAX_ROWS)):
             r1 = min(M, r0 + MAX_ROWS)
-            L.sr_linear_bwd(dy[r0:r1], w, a[r0:r1], self._q("dY_bwd", sdy, pos_dy + (r0 * N) // 8), saved["qw"],
-                            self._q("A_bwd", saved["sA"], saved["pos_a"] + (r0 * K) // 8), out_dA=da[r0:r1],
-                            out_dW=self.dW, beta=1.0 if self.have_grad else 0.0,
-                            workspace=self._workspace(L.OP_BWD, r1 - r0))
+            qdy = self._q("dY_bwd", sdy, pos_dy + (r0 * N) // 8)
+            qa = self._q("A_bwd", saved["sA"], saved["pos_a"] + (r0 * K) // 8)
+            beta = 1.0 if self.have_grad else 0.0
+            if "stash" in saved:
+                L.sr_linear_bwd_stashed(dy[r0:r1], saved["stash"][i], K, qdy, saved["qw"], qa, out_dA=da[r0:r1],
+                                        out_dW=self.dW, beta=beta, workspace=self._workspace(L.OP_BWD_STASHED, r1 - r0))
+            else:
+                L.sr_linear_bwd(dy[r0:r1], w, a[r0:r1], qdy, saved["qw"], qa, out_dA=da[r0:r1], out_dW=self.dW,
+                                beta=beta, workspace=self._workspace(L.OP_BWD, r1 - r0))
             self.have_grad = True
         return da
 
