@@ -183,7 +183,7 @@ __device__ __forceinline__ uint32_t abs_bits_finite(float f) {
 }
 
 // max of the finite |x_i| bit patterns over the 16-byte pieces [g0, g1) of x (4 binary32 or 8
-// bfloat16 elements each; the last piece of the tensor may be partial): thread t of nt, four loads in
+// bfloat16 elements each; the last piece of the tensor may be partial): thread t of nt, eight loads in
 // flight per lane, the pieces of a workgroup contiguous in memory
 template <int SRC>
 __device__ __forceinline__ uint32_t absmax_pieces(const void* __restrict__ x, size_t n, size_t g0, size_t g1, uint32_t t,
@@ -204,6 +204,13 @@ __device__ __forceinline__ uint32_t absmax_pieces(const void* __restrict__ x, si
     }
   };
   size_t i = g0 + t;
+  for (; i + 7 * (size_t)nt < gf; i += 8 * (size_t)nt) {
+    u32x4 a[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a[j] = __builtin_nontemporal_load(p + i + j * (size_t)nt);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) fold(a[j]);
+  }
   for (; i + 3 * (size_t)nt < gf; i += 4 * (size_t)nt) {
     const u32x4 a = __builtin_nontemporal_load(p + i), b = __builtin_nontemporal_load(p + i + nt);
     const u32x4 c = __builtin_nontemporal_load(p + i + 2 * (size_t)nt), d = __builtin_nontemporal_load(p + i + 3 * (size_t)nt);
