@@ -82,3 +82,10 @@ def test_ragged_layer_every_format(kind):
 def test_gpt2_fc1_benchmark_formats(kind):
     say("workspace codes fc1", L.KIND_NAMES[kind])
     _run(8192, 3072, 768, kind, seed=10, w_bf16=False)
+
+
+def test_many_row_bands_with_a_ragged_last_group():
+    # the transposing quantizer walks its tiles in groups of 16 bands of 128 rows: 37 full bands and
+    # a band of 16 rows make two full groups and one of six bands, the last of them partial
+    say("workspace codes, 4752 rows")
+    _run(4752, 144, 208, L.INT8, seed=5, w_bf16=True)
