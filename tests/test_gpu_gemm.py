@@ -249,12 +249,57 @@ def test_llama_shapes_int4_gradient_bf16_weights():
         _run_layer(t, _quants(kinds, t, seed=2), sample=65536)
 
 
+def _two_stream_stash_step(t, q):
+    """The benchmark's launch configuration: the stash pair in halves, the quantizing halves on one stream and
+    the products on another, events between them; returns Y, dA, dW."""
+    M, K = t["A"].shape
+    N = t["W"].shape[0]
+    dev = t["A"].device
+    stash = torch.empty(L.sr_linear_stash_bytes(M, N, K), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(L.sr_linear_workspace_bytes(L.OP_FWD_STASH, M, N, K), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(L.sr_linear_workspace_bytes(L.OP_BWD_STASHED, M, N, K), dtype=torch.uint8, device=dev)
+    Y = torch.zeros((M, N), dtype=torch.float32, device=dev)
+    dA = torch.zeros((M, K), dtype=torch.float32, device=dev)
+    dW = torch.zeros((N, K), dtype=torch.float32, device=dev)
+    fa = (t["A"], t["W"], q["A_fwd"][0], q["W_fwd"][0], q["A_bwd"][0], q["W_bwd"][0])
+    fk = dict(stash=stash, out=Y, workspace=ws_f)
+    ba = (t["dY"], stash, K, q["dY_bwd"][0], q["W_bwd"][0], q["A_bwd"][0])
+    bk = dict(out_dA=dA, out_dW=dW, workspace=ws_b)
+    mem, mat = torch.cuda.Stream(), torch.cuda.Stream()
+    ev_f, ev_b = torch.cuda.Event(), torch.cuda.Event()
+    cur = torch.cuda.current_stream()
+    mem.wait_stream(cur)
+    mat.wait_stream(cur)
+    with torch.cuda.stream(mem):
+        L.sr_linear_fwd_stash(*fa, phase=L.PHASE_QUANTIZE, **fk)
+        ev_f.record()
+        L.sr_linear_bwd_stashed(*ba, phase=L.PHASE_QUANTIZE, **bk)
+        ev_b.record()
+    with torch.cuda.stream(mat):
+        mat.wait_event(ev_f)
+        L.sr_linear_fwd_stash(*fa, phase=L.PHASE_PRODUCT, **fk)
+        mat.wait_event(ev_b)
+        L.sr_linear_bwd_stashed(*ba, phase=L.PHASE_PRODUCT, **bk)
+    cur.wait_stream(mem)
+    cur.wait_stream(mat)
+    torch.cuda.synchronize()
+    return Y, dA, dW
+
+
 def test_llama_projection_at_65536_tokens_sampled():
     # the largest token count of the sweep: 2^27-element activations and gradients, 256 x 256 tiles
     # for Y and dA, a 65536-long contraction for dW (int32 sums stay exact below 133143)
     kinds = {"A_fwd": L.INT8, "W_fwd": L.INT8, "A_bwd": L.INT8, "W_bwd": L.INT8, "dY_bwd": L.INT4}
     t = _layer(65536, 2048, 2048, 22, std_dy=1e-3, w_bf16=True)
-    _run_layer(t, _quants(kinds, t, seed=3), sample=16384)
+    q = _quants(kinds, t, seed=3)
+    _run_layer(t, q, sample=16384)
+    # the same layer as the benchmark launches it (two streams, stash pair in halves): the results just
+    # checked against the oracle, bit for bit
+    Y, dA, dW = _two_stream_stash_step(t, q)
+    assert torch.equal(Y, L.sr_linear_fwd(t["A"], t["W"], q["A_fwd"][0], q["W_fwd"][0]))
+    dA0, dW0 = L.sr_linear_bwd(t["dY"], t["W"], t["A"], q["dY_bwd"][0], q["W_bwd"][0], q["A_bwd"][0])
+    assert torch.equal(dA, dA0) and torch.equal(dW, dW0)
+    del Y, dA, dW, dA0, dW0
     # and the middle one with the two MLP shapes
     for N, K in ((5632, 2048), (2048, 5632)):
         t = _layer(16384, N, K, 23, std_dy=1e-3, w_bf16=True)
