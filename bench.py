@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="headline step and its roofline only (for profiling runs)")
-    ap.add_argument("--only", default="", help="run only this section (profiling runs): gpt2, products, fused, quantizer")
+    ap.add_argument("--only", default="", help="run only this section (profiling runs): step, gpt2, products, fused, quantizer")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB device copy (known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -571,6 +571,19 @@ def main():
             out = {"sr_quantize": quantizer_sweep(L, synth, torch, max(5, args.steps // 5))}
         elif args.only == "products":
             out = {"roofline": llama_products_roofline(L, torch, max(5, args.steps // 2))}
+        elif args.only == "step":
+            # the headline step alone: warm-up + steps on two streams, then the same in one stream
+            layers = llama_layers(L, synth, torch, TOKENS, synth.LLAMA_1B_LINEARS)
+            two = TwoStreamStep(torch, L, layers)
+
+            def one():
+                for ly in layers:
+                    ly.step(L)
+            flops = sum(ly.flops() for ly in layers)
+            out = {}
+            for name, fn in (("two_streams", two), ("single_stream", one)):
+                sec = time_steps(torch, fn, args.steps, args.warmup)
+                out[name] = {"ms_per_step": round(sec * 1e3, 4), "TFLOP/s": round(flops / sec / 1e12, 1)}
         else:
             print("unknown section " + args.only, file=sys.stderr)
             sys.exit(2)
