@@ -87,6 +87,7 @@ QuantJob make_job(const srq_quant* q, const void* x, int dtype, size_t rows, siz
   j.counter_offset = counter_host(q); j.counter_dev = counter_dev(q);
   j.kind2 = 0; j.round2 = SRQ_SR; j.scale2 = 1.0f; j.scale_dev2 = nullptr; j.seed2 = j.counter_offset2 = 0;
   j.counter_dev2 = nullptr;
+  j.pack_t = j.pack_2 = 0;
   j.first_block = j.nblocks = 0;
   return j;
 }
@@ -162,10 +163,11 @@ bool workspace_ok(const void* ws, size_t have, size_t need) {
 
 int launch_product(float* out, const uint8_t* xc, const srq_quant* qx, const uint8_t* zc, const srq_quant* qz,
                    size_t P, size_t Q, size_t R, const ProductPlan& pp, float beta, void* gws, hipStream_t s,
-                   const SliceSum* carry = nullptr, SliceSum* defer = nullptr) {
-  GemmScale sc{1.0f, qx->scale, qz->scale, qx->scale_dev, qz->scale_dev};
+                   const SliceSum* carry = nullptr, SliceSum* defer = nullptr, bool x_packed = false) {
+  // packed 4-bit X: the kernel multiplies 16 * value, the factor goes into alpha (a power of two: exact)
+  GemmScale sc{x_packed ? 0.0625f : 1.0f, qx->scale, qz->scale, qx->scale_dev, qz->scale_dev};
   return launch_gemm_codes(out, xc, qx->kind, zc, qz->kind, P, Q, R, R * pp.es, pp.pipe, sc, beta == 1.0f, gws,
-                           s, carry, defer) == hipSuccess
+                           s, carry, defer, x_packed) == hipSuccess
              ? SRQ_OK
              : SRQ_ERR_HIP;
 }
@@ -177,15 +179,29 @@ int launch_product(float* out, const uint8_t* xc, const srq_quant* qx, const uin
 int launch_backward_products(float* dA, float* dW, const uint8_t* dy_rm, const uint8_t* w_t, const uint8_t* dy_t,
                              const uint8_t* a_t, const srq_quant* qdY, const srq_quant* qW, const srq_quant* qA,
                              size_t M, size_t N, size_t K, const ProductPlan& pd, const ProductPlan& pw, float beta,
-                             void* gws_d, void* gws_w, hipStream_t s) {
+                             void* gws_d, void* gws_w, hipStream_t s, bool packed_rm = false,
+                             bool packed_t = false) {
   SliceSum sum_w{};
-  int st = launch_product(dW, dy_t, qdY, a_t, qA, N, K, M, pw, beta, gws_w, s, nullptr, &sum_w);
+  int st = launch_product(dW, dy_t, qdY, a_t, qA, N, K, M, pw, beta, gws_w, s, nullptr, &sum_w, packed_t);
   if (st != SRQ_OK) return st;
-  st = launch_product(dA, dy_rm, qdY, w_t, qW, M, K, N, pd, 0.0f, gws_d, s, &sum_w, nullptr);
+  st = launch_product(dA, dy_rm, qdY, w_t, qW, M, K, N, pd, 0.0f, gws_d, s, &sum_w, nullptr, packed_rm);
   // the weight gradient is already enqueued: if the launch that was to carry its slice sum
   // failed, finish it in a launch of its own so that dW is whole whatever happens to dA
   if (st != SRQ_OK) (void)launch_slice_sum(sum_w, s);
   return st;
+}
+
+// A 4-bit output gradient from a binary32 source is written two values per byte for the products that
+// take it so (the int8 pipeline on 256 x 256 tiles): half the bytes written, and read, of the
+// operand every backward product shares.  rm: the copy in the source layout (X of dA, M x N);
+// t: the transposed copy (X of dW, N x M).
+struct PackedDy {
+  bool rm, t;
+};
+PackedDy packed_dy(const srq_quant* qdY, int dtypedY, const ProductPlan& pd, const ProductPlan& pw, size_t M, size_t N,
+                   size_t K) {
+  const bool nib = dtypedY == SRQ_F32 && qdY->kind == SRQ_INT4 && pd.pipe == PIPE_I8 && pw.pipe == PIPE_I8;
+  return PackedDy{nib && gemm_takes_packed_x(M, K, N, PIPE_I8), nib && gemm_takes_packed_x(N, K, M, PIPE_I8)};
 }
 
 // One product of Alg. 1 / Alg. 2: quantize both operands into the workspace (one launch) with
@@ -615,12 +631,15 @@ int sr_linear_bwd_phase(float* dA, float* dW, const void* dY, int dtypedY, const
   QuantJobs jobs;
   jobs.njobs = 3;
   jobs.job[0] = make_job(qdY_bwd, dY, dtypedY, M, N, 1, store, dy_t, dy_rm);
+  const PackedDy pk = packed_dy(qdY_bwd, dtypedY, pd, pw, M, N, K);
+  jobs.job[0].pack_2 = pk.rm;
+  jobs.job[0].pack_t = pk.t;
   jobs.job[1] = make_job(qW_bwd, W, dtypeW, N, K, 1, store, w_t, nullptr);
   jobs.job[2] = make_job(qA_bwd, A, dtypeA, M, K, 1, store, a_t, nullptr);
   if ((phase & SRQ_PHASE_QUANTIZE) && launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
   if (!(phase & SRQ_PHASE_PRODUCT)) return SRQ_OK;
   return launch_backward_products(dA, dW, dy_rm, w_t, dy_t, a_t, qdY_bwd, qW_bwd, qA_bwd, M, N, K, pd, pw, beta, gws_d,
-                                  gws_w, s);
+                                  gws_w, s, pk.rm, pk.t);
 }
 
 // Eq. 10 with bfloat16 weights.
@@ -739,10 +758,13 @@ int sr_linear_bwd_stashed_phase(float* dA, float* dW, const void* dY, int dtyped
   QuantJobs jobs;
   jobs.njobs = 1;
   jobs.job[0] = make_job(qdY_bwd, dY, dtypedY, M, N, 1, store, dy_t, dy_rm);
+  const PackedDy pk = packed_dy(qdY_bwd, dtypedY, pd, pw, M, N, K);
+  jobs.job[0].pack_2 = pk.rm;
+  jobs.job[0].pack_t = pk.t;
   if ((phase & SRQ_PHASE_QUANTIZE) && launch_quantize_jobs(jobs, s) != hipSuccess) return SRQ_ERR_HIP;
   if (!(phase & SRQ_PHASE_PRODUCT)) return SRQ_OK;
   return launch_backward_products(dA, dW, dy_rm, w_t, dy_t, a_t, qdY_bwd, qW_bwd, qA_bwd, M, N, K, pd, pw, beta, gws_d,
-                                  gws_w, s);
+                                  gws_w, s, pk.rm, pk.t);
 }
 
 const char* sr_status_string(int status) {

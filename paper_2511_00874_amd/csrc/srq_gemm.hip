@@ -31,6 +31,7 @@ namespace srq {
 namespace {
 
 using namespace mma;
+typedef int v2i __attribute__((ext_vector_type(2)));
 
 struct GemmParams {
   float* out;            // P x Q (final) -- or partial sums when nsplit > 1
@@ -39,6 +40,7 @@ struct GemmParams {
   const uint8_t* Z;
   uint32_t P, Q, R;      // R: bytes per operand row (contraction length x element size)
   uint32_t pitch;        // bytes between operand rows (>= R, multiple of 16)
+  uint32_t pitch_x;      // the same for X when its rows hold two 4-bit values per byte (else = pitch)
   uint32_t k_per_split;  // bytes of R per z-slice, multiple of BK
   uint32_t nsplit;
   uint32_t tiles_p, tiles_q;
@@ -418,13 +420,20 @@ struct TileItem {
   uint32_t valid, p0, q0, slice, kbeg, kend;
 };
 
-template <class MMA>
+// XP: the X operand holds 4-bit integers, two per byte ("packed": byte j of every 8 holds elements j
+// and j + 8 of a run of 16 along the contraction, low and high nibble).  Its rows take 64 bytes of
+// a stage, half the DMA instructions, and half the LDS bytes per fragment; a fragment is widened in
+// registers to the bytes 16 * value (shift / mask: the nibble's sign bit becomes the byte's), so
+// the accumulators hold 16 times the sums and the caller passes alpha / 16 -- powers of two, the
+// results are bit for bit those of the one-byte form.
+template <class MMA, bool XP>
 __global__ __launch_bounds__(512) void gemm_nt_persist_kernel(GemmParams g, SliceSum rider) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
   constexpr int BM = 256, BN = 256, WGN = 4, NW = 8, NLOAD = 4;
   constexpr int WTM = 128, WTN = 64, TM = WTM / 32, TN = WTN / 32;
   constexpr int STAGE = (BM + BN) * BK;
-  constexpr int XL = BM / 8 / NLOAD, ZL = BN / 8 / NLOAD;  // DMA instructions per loader wave and stage
+  // DMA instructions per loader wave and stage (an instruction covers 8 rows of 128 bytes, or 16 packed rows of 64)
+  constexpr int XL = XP ? BM / 16 / NLOAD : BM / 8 / NLOAD, ZL = BN / 8 / NLOAD;
   static_assert(XL % 2 == 0 && ZL % 2 == 0, "row blocks of a wave must start at an even block");
   static_assert(XL + ZL <= 63, "vmcnt range");
   using acc_t = typename MMA::acc_t;
@@ -432,6 +441,7 @@ __global__ __launch_bounds__(512) void gemm_nt_persist_kernel(GemmParams g, Slic
   using raw_t = typename MMA::raw_t;
   constexpr int FC = sizeof(raw_t) / 16;
   constexpr int KSUB = BK / MMA::KSTEP;
+  static_assert(!XP || (FC == 1 && sizeof(frag_t) == 16 && MMA::KSTEP == 32), "packed X: the int8 pipeline only");
 
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -464,7 +474,7 @@ __global__ __launch_bounds__(512) void gemm_nt_persist_kernel(GemmParams g, Slic
   };
 
   const __amdgpu_buffer_rsrc_t xrsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.X), 0, (int)(g.P * g.pitch), 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.X), 0, (int)(g.P * g.pitch_x), 0x00020000);
   const __amdgpu_buffer_rsrc_t zrsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.Z), 0, (int)(g.Q * g.pitch), 0x00020000);
 
@@ -481,10 +491,21 @@ __global__ __launch_bounds__(512) void gemm_nt_persist_kernel(GemmParams g, Slic
     const bool live0 = it.kbeg + kc0 < it.kend, live1 = it.kbeg + kc1 < it.kend;
     const uint32_t xs = lds_base + buf * STAGE + wave_u * XL * 1024;
     const uint32_t zs = lds_base + buf * STAGE + BM * BK + wave_u * ZL * 1024;
+    if constexpr (XP) {
+      // packed rows: 64 bytes of a row per stage, 16 rows per instruction; lane L fetches row L / 4
+      // and the logical 16-byte chunk whose physical slot is L % 4 (chunk c of row r is stored at
+      // chunk c ^ ((r >> 2) & 3)); a chunk holds 32 elements of the contraction
+      const uint32_t pchunk = (ln & 3u) ^ ((ln >> 4) & 3u);
+      const uint32_t xvp = (it.p0 + wave * XL * 16 + (ln >> 2)) * g.pitch_x + ((it.kbeg + koff) >> 1) + pchunk * 16;
+      const bool livep = it.kbeg + koff + pchunk * 32 < it.kend;
 #pragma unroll
-    for (int i = 0; i < XL; ++i)
-      lds_dma16(xrsrc, xs + i * 1024,
-                (i & 1) ? (live1 ? xvoff + kc1 + i * 8 * g.pitch : OOB) : (live0 ? xvoff + kc0 + i * 8 * g.pitch : OOB));
+      for (int i = 0; i < XL; ++i) lds_dma16(xrsrc, xs + i * 1024, livep ? xvp + i * 16 * g.pitch_x : OOB);
+    } else {
+#pragma unroll
+      for (int i = 0; i < XL; ++i)
+        lds_dma16(xrsrc, xs + i * 1024,
+                  (i & 1) ? (live1 ? xvoff + kc1 + i * 8 * g.pitch : OOB) : (live0 ? xvoff + kc0 + i * 8 * g.pitch : OOB));
+    }
 #pragma unroll
     for (int i = 0; i < ZL; ++i)
       lds_dma16(zrsrc, zs + i * 1024,
@@ -499,6 +520,11 @@ __global__ __launch_bounds__(512) void gemm_nt_persist_kernel(GemmParams g, Slic
     xoff[t] = (wp * WTM + (lane & 31u)) * BK + ((swz ^ tt) << 4);
     zoff[t] = BM * BK + (wq * WTN + (lane & 31u)) * BK + ((swz ^ tt) << 4);
   }
+  // packed X: 8 bytes per lane and MFMA (16 elements), row pitch 64, chunk ks of row r at ks ^ ((r >> 2) & 3)
+  uint32_t xoffp[KSUB];
+#pragma unroll
+  for (int ks = 0; ks < KSUB; ++ks)
+    xoffp[ks] = (wp * WTM + (lane & 31u)) * 64u + ((((uint32_t)ks ^ (lane >> 2)) & 3u) << 4) + 8u * (lane >> 5);
   auto load_frag = [&](const uint8_t* stage, const uint32_t (&off)[KSUB * FC], int sub, int ks) {
     raw_t f;
 #pragma unroll
@@ -517,10 +543,14 @@ __global__ __launch_bounds__(512) void gemm_nt_persist_kernel(GemmParams g, Slic
   constexpr int PF = 1;
   auto compute = [&](uint32_t buf) {
     const uint8_t* stage = lds + buf * STAGE;
-    raw_t xf[PF + 1][TM], zf[PF + 1][TN];
+    typename std::conditional<XP, v2i, raw_t>::type xf[PF + 1][TM];
+    raw_t zf[PF + 1][TN];
     auto fetch = [&](int ks) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) xf[ks % (PF + 1)][i] = load_frag(stage, xoff, i, ks);
+      for (int i = 0; i < TM; ++i) {
+        if constexpr (XP) xf[ks % (PF + 1)][i] = *reinterpret_cast<const v2i*>(stage + xoffp[ks] + i * 32 * 64);
+        else xf[ks % (PF + 1)][i] = load_frag(stage, xoff, i, ks);
+      }
 #pragma unroll
       for (int j = 0; j < TN; ++j) zf[ks % (PF + 1)][j] = load_frag(stage, zoff, j, ks);
     };
@@ -532,7 +562,16 @@ __global__ __launch_bounds__(512) void gemm_nt_persist_kernel(GemmParams g, Slic
       __builtin_amdgcn_sched_barrier(0);
       frag_t xe[TM], ze[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) xe[i] = MMA::expand(xf[ks % (PF + 1)][i]);
+      for (int i = 0; i < TM; ++i) {
+        if constexpr (XP) {
+          // byte j of the 8 holds elements j (low nibble) and j + 8 (high nibble): four words of 16 * value
+          const v2i x = xf[ks % (PF + 1)][i];
+          const int hi = (int)0xF0F0F0F0u;
+          xe[i] = frag_t{(x[0] << 4) & hi, (x[1] << 4) & hi, x[0] & hi, x[1] & hi};
+        } else {
+          xe[i] = MMA::expand(xf[ks % (PF + 1)][i]);
+        }
+      }
 #pragma unroll
       for (int j = 0; j < TN; ++j) ze[j] = MMA::expand(zf[ks % (PF + 1)][j]);
 #pragma unroll
@@ -808,10 +847,10 @@ hipError_t launch_tile(GemmParams g, const SliceSumPlan& ss, hipStream_t stream)
 
 // The 256 x 256 tiles on workgroups that stay (gemm_nt_persist_kernel): one workgroup per CU, or
 // fewer if there is less work.
-template <class MMA>
+template <class MMA, bool XP = false>
 hipError_t launch_persist(GemmParams g, const SliceSumPlan& ss, hipStream_t stream) {
   constexpr int LDS_BYTES = 2 * (256 + 256) * BK;
-  auto kern = &gemm_nt_persist_kernel<MMA>;
+  auto kern = &gemm_nt_persist_kernel<MMA, XP>;
   static const hipError_t configured = hipFuncSetAttribute(
       reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   if (configured != hipSuccess) return configured;
@@ -855,6 +894,10 @@ size_t gemm_workspace_bytes(size_t P, size_t Q, size_t R, int pipe) {
   return pl.nsplit > 1 ? (size_t)pl.nsplit * P * Q * sizeof(uint32_t) : 0;
 }
 
+bool gemm_takes_packed_x(size_t P, size_t Q, size_t R, int pipe) {
+  return pipe == PIPE_I8 && make_plan(P, Q, R).tile == 0;
+}
+
 bool gemm_operands_addressable(size_t P, size_t Q, size_t R, int pipe) {
   const size_t rb = pipe == PIPE_BF16 ? 2 * R : R;
   return (P + 256) * rb < (1ull << 31) && (Q + 256) * rb < (1ull << 31);
@@ -863,21 +906,24 @@ bool gemm_operands_addressable(size_t P, size_t Q, size_t R, int pipe) {
 hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint8_t* Z, int kindZ,
                              size_t P, size_t Q, size_t R, size_t pitch, int pipe, const GemmScale& s,
                              bool accumulate, void* workspace, hipStream_t stream, const SliceSum* carry,
-                             SliceSum* defer) {
+                             SliceSum* defer, bool x_packed) {
   const SliceSumPlan ss{carry, defer};
   const size_t row_bytes = pipe == PIPE_BF16 ? 2 * R : R;
   const Plan pl = make_plan(P, Q, row_bytes);
+  if (x_packed && !(pipe == PIPE_I8 && pl.tile == 0)) return hipErrorInvalidValue;  // see gemm_takes_packed_x
   GemmParams g;
   g.out = out;
   g.partial = static_cast<uint32_t*>(workspace);
   g.X = X; g.Z = Z;
   g.P = (uint32_t)P; g.Q = (uint32_t)Q; g.R = (uint32_t)row_bytes;
   g.pitch = (uint32_t)pitch;
+  g.pitch_x = (uint32_t)(x_packed ? pitch / 2 : pitch);
   g.k_per_split = pl.k_per_split;
   g.nsplit = pl.nsplit;
   g.tiles_p = g.tiles_q = 0;
   g.alpha = s.alpha; g.sx = s.sx; g.sz = s.sz; g.sx_dev = s.sx_dev; g.sz_dev = s.sz_dev;
   g.accumulate = accumulate ? 1 : 0;
+  if (x_packed) return launch_persist<I8Mma, true>(g, ss, stream);
   if (pipe == PIPE_I8) return launch_mma<I8Mma>(g, pl, ss, stream);
   if (pipe == PIPE_BF16) return launch_mma<BF16Mma>(g, pl, ss, stream);
   if (pipe == PIPE_F16C) return launch_mma<E5M2F16Mma>(g, pl, ss, stream);

@@ -48,6 +48,10 @@ struct QuantJob {
   const float* scale_dev2;
   uint64_t seed2, counter_offset2;
   const uint64_t* counter_dev2;
+  // SRQ_INT4 from a binary32 source, transposing jobs: write the transposed output (pack_t) or the
+  // same-codes output in the source layout (pack_2, kind2 == 0) two values per byte, in the form
+  // gemm_takes_packed_x describes (runs of 16 along rows, respectively along columns)
+  int pack_t, pack_2;
   uint32_t first_block, nblocks;  // filled by the launcher
 };
 struct QuantJobs {
@@ -125,7 +129,12 @@ struct SliceSum {
 hipError_t launch_gemm_codes(float* out, const uint8_t* X, int kindX, const uint8_t* Z, int kindZ,
                              size_t P, size_t Q, size_t R, size_t pitch, int pipe, const GemmScale& s,
                              bool accumulate, void* workspace, hipStream_t stream,
-                             const SliceSum* carry = nullptr, SliceSum* defer = nullptr);
+                             const SliceSum* carry = nullptr, SliceSum* defer = nullptr, bool x_packed = false);
+// x_packed: X holds 4-bit integers two per byte -- byte j of every 8 holds elements j (low nibble)
+// and j + 8 (high nibble) of a run of 16 along the contraction -- in rows of pitch / 2 bytes, and
+// s.alpha carries a factor 1/16 (the kernel multiplies 16 * value).  Only where
+// gemm_takes_packed_x says so: the int8 pipeline on the 256 x 256 tiles.
+bool gemm_takes_packed_x(size_t P, size_t Q, size_t R, int pipe);
 // a deferred slice sum that found no later launch to ride on
 hipError_t launch_slice_sum(const SliceSum& r, hipStream_t stream);
 

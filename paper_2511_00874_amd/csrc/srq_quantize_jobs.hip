@@ -142,6 +142,17 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
           uint16_t* o = reinterpret_cast<uint16_t*>(j.out2);
           if (okA) store_through8(o + eA, u32x2{ca[0] | (ca[1] << 16), ca[2] | (ca[3] << 16)});
           if (okB) store_through8(o + eB, u32x2{cb[0] | (cb[1] << 16), cb[2] | (cb[3] << 16)});
+        } else if (KIND == SRQ_INT4 && j.pack_2) {
+          // two values per byte: four lanes hold a run of 16 columns (cols % 16 == 0: whole runs);
+          // byte j of its 8 takes element j in the low and element j + 8 in the high nibble, so the
+          // lanes with elements 0-7 take the nibbles of the lane two further on and write 4 bytes each
+          const uint32_t na = pack4_bytes(ca) & 0x0F0F0F0Fu, nb = pack4_bytes(cb) & 0x0F0F0F0Fu;
+          const uint32_t pa = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)na, 0x4E, 0xF, 0xF, true);
+          const uint32_t pb = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)nb, 0x4E, 0xF, 0xF, true);
+          if (!(lane & 2u)) {
+            if (okA) store_through4(j.out2 + (eA >> 1) + 2u * (lane & 1u), na | (pa << 4));
+            if (okB) store_through4(j.out2 + (eB >> 1) + 2u * (lane & 1u), nb | (pb << 4));
+          }
         } else {
           if (okA) store_through4(j.out2 + eA, pack4_bytes(ca));
           if (okB) store_through4(j.out2 + eB, pack4_bytes(cb));
@@ -211,6 +222,13 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
     const uint32_t col = c0 + c, row = r0 + ch * 16;
     if (col >= cols || row >= rows) continue;  // rows % 16 == 0 for the linear entry points
     const uint32_t* src = reinterpret_cast<const uint32_t*>(&tile[c * PITCH + ch * 16]);
+    if (KIND == SRQ_INT4 && !AS_BF16 && j.pack_t) {
+      // two values per byte along the transposed row: byte j of 8 = elements j and j + 8 of the 16
+      const uint32_t m = 0x0F0F0F0Fu;
+      store_through8(j.out + (((size_t)col * rows + row) >> 1),
+                     u32x2{(src[0] & m) | ((src[2] & m) << 4), (src[1] & m) | ((src[3] & m) << 4)});
+      continue;
+    }
     elem_t* dst = reinterpret_cast<elem_t*>(j.out) + (size_t)col * rows + row;
 #pragma unroll
     for (int i = 0; i < ES; ++i)

@@ -4,7 +4,8 @@ launch (same-layout, transposing, two-output and bfloat16-valued forms), not fro
 
 Workspace layout (pieces aligned to 256 bytes): forward  [Q(A) M x K | Q(W) N x K | slices];
 whole backward pass  [Q(dY) M x N | Q(W)^T K x N | slices | Q(dY)^T N x M | Q(A)^T K x M | slices].
-An operand is one byte per element (integer formats: the value, int4 too; E5M2 when every operand
+An operand is one byte per element (integer formats: the value; a 4-bit dY from a binary32 source is
+stored two per byte for the products that run on 256 x 256 tiles; E5M2 when every operand
 of the call is E5M2: the code) or the grid value as bfloat16."""
 import numpy as np
 import pytest
@@ -89,3 +90,50 @@ def test_many_row_bands_with_a_ragged_last_group():
     # a band of 16 rows make two full groups and one of six bands, the last of them partial
     say("workspace codes, 4752 rows")
     _run(4752, 144, 208, L.INT8, seed=5, w_bf16=True)
+
+
+def _nib16(codes):
+    """Two 4-bit values per byte: byte j of every 8 holds elements j (low nibble) and j + 8 (high nibble)
+    of a run of 16 along the last axis."""
+    r = (codes.view(np.uint8) & 0x0F).reshape(codes.shape[0], -1, 2, 8)
+    return (r[:, :, 0, :] | (r[:, :, 1, :] << 4)).reshape(codes.shape[0], -1)
+
+
+# the benchmark's layer shape at 16384 tokens; ragged shapes whose products take the 256 x 256 tiles, with
+# contractions that end half way through a 16-byte piece of packed values (length % 32 == 16), one of
+# them long enough to be cut into slices
+@pytest.mark.parametrize("M,N,K", [(16384, 2048, 2048), (8208, 1040, 4112), (32784, 2064, 1040), (6160, 1040, 4112)])
+def test_four_bit_gradient_is_stored_two_per_byte_for_the_large_tile_products(M, N, K):
+    # Llama formats (int4 dY, int8 elsewhere), binary32 dY: where a backward product runs on the 256 x 256
+    # tiles its copy of Q(dY) is written two values per byte; elsewhere one per byte.  Either way the
+    # values are the oracle's, and for the benchmark's layer shape both copies are packed.
+    say("workspace codes, packed int4 dY", M, N, K)
+    A, W, dY = synth.single_layer(M, N, K, 9, std_dy=1e-3)
+    A, W, dY = to_dev(A), to_dev(W, True), to_dev(dY)
+    q = {}
+    off = 0
+    for name, t, kind in (("dY", dY, L.INT4), ("W", W, L.INT8), ("A", A, L.INT8)):
+        q[name] = oracle.Quant(kind, oracle.absmax_scale(host_src(t), kind), 4, off)
+        off += (t.numel() + 7) // 8
+    lq = {n: L.Quant(v.kind, v.scale, v.seed, v.counter_offset) for n, v in q.items()}
+    ws = torch.zeros(L.sr_linear_workspace_bytes(L.OP_BWD, M, N, K), dtype=torch.uint8, device=A.device)
+    dA, dW = L.sr_linear_bwd(dY, W, A, lq["dY"], lq["W"], lq["A"], workspace=ws)
+    codes = oracle.quantize(host_src(dY), L.INT4, q["dY"].scale, q["dY"].seed, q["dY"].counter_offset)
+    slices = L.sr_gemm_workspace_bytes
+    o_dy = 0
+    o_dyt = _up(M * N) + _up(K * N) + _up(slices(M, K, N))
+    packed = []
+    for name, off_b, c in (("Q(dY)", o_dy, codes), ("Q(dY)^T", o_dyt, np.ascontiguousarray(codes.T))):
+        got = _piece(ws, off_b, M * N)
+        if np.array_equal(got, c.reshape(-1)):
+            packed.append(False)
+        else:
+            assert np.array_equal(got[:M * N // 2], _nib16(c).reshape(-1)), name
+            packed.append(True)
+    if (M, N, K) == (16384, 2048, 2048):
+        assert packed == [True, True]
+    assert any(packed)   # (which products take the large tiles is the cost model's choice; these shapes do today)
+    # and the products from them are those of the separate calls (one value per byte) bit for bit
+    assert torch.equal(dA, L.sr_linear_bwd_data(dY, W, lq["dY"], lq["W"]))
+    assert torch.equal(dW, L.sr_linear_bwd_weight(dY, A, lq["dY"], lq["A"]))
+    say("   packed:", packed)
