@@ -28,7 +28,7 @@ GPT2_TOKENS = 8192
 # Bytes moved behind the L2 per launch of the dominant kernel (int8 product, 256 x 256 tiles) on the nine
 # products of the headline workload, slice sums included: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by
 # what the same counters read for a plain copy of known size (profiles/product_int8_llama_hbm_traffic.txt)
-TRAFFIC_I8_PRODUCT_LLAMA = 1633435720
+TRAFFIC_I8_PRODUCT_LLAMA = 1392612286
 TRAFFIC_QUANTIZE_INT8_2P28 = (1024.0 + 256.0) * 2**20
 
 
@@ -212,42 +212,46 @@ def llama_layers(L, synth, torch, T, shapes, seed0=7):
             for i, (nm, N, K) in enumerate(shapes)]
 
 
-def llama_products_roofline(L, torch, reps):
-    """The dominant kernel of the headline step alone: the int8 product kernel on the nine products
-    of the three distinct layer shapes at 65536 tokens (operands already quantized), timed by HIP
-    events on the stream it is launched on."""
-    dev = "cuda:0"
+def llama_products_roofline(L, synth, torch, reps):
+    """The dominant kernel of the headline step alone: the nine product launches of the three distinct
+    layer shapes at 65536 tokens -- forward product, weight-gradient product, input-gradient product
+    (which also carries the sum of the weight gradient's contraction slices) -- as the step issues
+    them (product halves of the stash pair), from the operands the step's quantizers wrote: int8
+    codes, the 4-bit output gradient two values per byte.  Timed by HIP events on the launch stream."""
     T = TOKENS
-    shapes = []
-    for N, K in ((2048, 2048), (5632, 2048), (2048, 5632)):
-        shapes += [(T, N, K), (T, K, N), (N, K, T)]  # Y, dA, dW as out (P x Q), contraction R
-    calls, flops, alg_bytes = [], 0.0, 0.0
-    for (P, Q, R) in shapes:
-        need = L.raw.sr_gemm_workspace_bytes(P, Q, R)
-        X = torch.randint(-127, 128, (P, R), dtype=torch.int8, device=dev).view(torch.uint8)
-        Z = torch.randint(-127, 128, (Q, R), dtype=torch.int8, device=dev).view(torch.uint8)
-        calls.append((X, Z, torch.empty((P, Q), dtype=torch.float32, device=dev),
-                      torch.empty(max(need, 16), dtype=torch.uint8, device=dev)))
-        flops += 2.0 * P * Q * R
-        alg_bytes += P * R + Q * R + 4.0 * P * Q
+    shapes = [synth.LLAMA_1B_LINEARS[i] for i in (0, 4, 6)]
+    layers = llama_layers(L, synth, torch, T, shapes)
+    flops = alg_bytes = 0.0
+    for ly in layers:
+        ly.absmax.run()
+        ly.forward_phase(L, L.PHASE_QUANTIZE)
+        ly.backward(L, L.PHASE_QUANTIZE)
+        M, N, K = ly.M, ly.N, ly.K
+        flops += 6.0 * M * N * K
+        # operands once (Q(dY) at half a byte per element) + the fp32 result once, per product
+        alg_bytes += (M * K + N * K + 4.0 * M * N) + (M * N / 2 + K * N + 4.0 * M * K) + (N * M / 2 + K * M + 4.0 * N * K)
+    torch.cuda.synchronize()
 
     def run():
-        for X, Z, o, ws in calls:
-            L.sr_gemm_codes(X, L.INT8, Z, L.INT8, out=o, workspace=ws)
-    ms = event_ms(torch, run, reps) / len(calls)
-    fl = flops / len(calls)
+        for ly in layers:
+            ly.forward_phase(L, L.PHASE_PRODUCT)
+            ly.backward(L, L.PHASE_PRODUCT)
+    launches = 3 * len(layers)
+    ms = event_ms(torch, run, reps) / launches
+    fl = flops / launches
     tf = fl / (ms * 1e-3) / 1e12
-    del calls
+    del layers
     torch.cuda.empty_cache()
-    return {"bound": "mfma", "kernel": "gemm_nt_persist_kernel<I8Mma> (int8 codes, int32 accumulators, 256 x 256 tiles "
-                                       "on workgroups that stay)",
+    return {"bound": "mfma", "kernel": "gemm_nt_persist_kernel<I8Mma, *> (int8 codes, 4-bit X two per byte in the backward "
+                                       "products, int32 accumulators, 256 x 256 tiles on workgroups that stay)",
             "achieved": round(tf, 1), "peak": MFMA_PEAK_TFLOPS["int8"], "unit": "TFLOP/s",
             "frac": round(tf / MFMA_PEAK_TFLOPS["int8"], 4), "traffic": TRAFFIC_I8_PRODUCT_LLAMA,
-            "launches": len(shapes), "avg_launch_us": round(ms * 1e3, 2), "flop_per_launch": fl,
-            "algorithmic_bytes_per_launch": alg_bytes / len(shapes),
-            "note": "mean over the nine products (Y, dA, dW of the 2048x2048, 5632x2048 and 2048x5632 layers at "
-                    "65536 tokens), operands already quantized; algorithmic bytes = both operands once + the "
-                    "fp32 result once; the weight-gradient launches include the sum of their contraction slices"}
+            "launches": launches, "avg_launch_us": round(ms * 1e3, 2), "flop_per_launch": fl,
+            "algorithmic_bytes_per_launch": alg_bytes / launches,
+            "note": "mean over the nine product launches (Y, dW, dA of the 2048x2048, 5632x2048 and 2048x5632 layers at "
+                    "65536 tokens) as the step issues them, on the operands its quantizers wrote; algorithmic bytes = "
+                    "both operands once + the fp32 result once; the input-gradient launches carry the sum of the "
+                    "weight gradient's contraction slices"}
 
 
 def fused_prologue(L, synth, torch, reps):
@@ -570,7 +574,7 @@ def main():
         elif args.only == "quantizer":
             out = {"sr_quantize": quantizer_sweep(L, synth, torch, max(5, args.steps // 5))}
         elif args.only == "products":
-            out = {"roofline": llama_products_roofline(L, torch, max(5, args.steps // 2))}
+            out = {"roofline": llama_products_roofline(L, synth, torch, max(5, args.steps // 2))}
         elif args.only == "step":
             # the headline step alone: warm-up + steps on two streams, then the same in one stream
             layers = llama_layers(L, synth, torch, TOKENS, synth.LLAMA_1B_LINEARS)
@@ -642,7 +646,7 @@ def main():
         "per_shape": per_shape,
         "phases": phases,
     }
-    line["roofline"] = llama_products_roofline(L, torch, max(5, args.steps // 2))
+    line["roofline"] = llama_products_roofline(L, synth, torch, max(5, args.steps // 2))
     if not args.no_extras:
         line["token_sweep"] = token_sweep(L, synth, torch)
         line["gpt2_mlp"] = gpt2_mlp(L, synth, torch, args.steps, args.warmup)
