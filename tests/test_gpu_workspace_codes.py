@@ -136,4 +136,8 @@ def test_four_bit_gradient_is_stored_two_per_byte_for_the_large_tile_products(M,
     # and the products from them are those of the separate calls (one value per byte) bit for bit
     assert torch.equal(dA, L.sr_linear_bwd_data(dY, W, lq["dY"], lq["W"]))
     assert torch.equal(dW, L.sr_linear_bwd_weight(dY, A, lq["dY"], lq["A"]))
+    # accumulation onto the weight gradient (beta = 1) through the packed products and their slice sums
+    acc = dW.clone()
+    L.sr_linear_bwd(dY, W, A, lq["dY"], lq["W"], lq["A"], out_dA=dA, out_dW=acc, beta=1.0, workspace=ws)
+    assert torch.equal(acc, dW + dW)
     say("   packed:", packed)
