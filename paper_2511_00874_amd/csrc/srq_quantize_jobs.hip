@@ -14,7 +14,15 @@ namespace srq {
 namespace {
 
 constexpr int QBLOCK = 256;
-constexpr int TR = 128, TC = 64;        // transposing tile: TR source rows x TC source columns
+constexpr int TC = 64;                  // transposing tile: tile_rows source rows x TC source columns
+// Tile rows: 128, or 256 for one-byte codes of a tensor large enough to give every CU several such
+// tiles (the same 16.6 KB of LDS as 128 rows of bfloat16 values).  A workgroup then writes 256 bytes
+// of every transposed row (128 where two 4-bit values share a byte): whole cache lines.  Small
+// tensors keep 128 rows: twice the workgroups (GPT-2 sizes lose 4 % of their step with 256).
+__host__ __device__ inline int tile_rows(bool as_bf16, uint32_t rows, uint32_t cols) {
+  return !as_bf16 && (size_t)((rows + 255u) / 256u) * ((cols + TC - 1) / TC) >= 2048u ? 256 : 128;
+}
+constexpr size_t STREAM_OUT_BYTES = 64u << 20;
 constexpr int BAND_GROUP = 16;          // row bands whose tiles are walked together (tile order)
 constexpr int FLAT_GROUPS_PER_BLOCK = QBLOCK * 4;  // sixteen 512-element chunks: four per wave (measured best of 1, 2, 4, 8)
 
@@ -48,7 +56,7 @@ __device__ __forceinline__ void store_group(uint8_t* out, size_t base, const uin
 // binary32 sources go chunk-wise (one fully coalesced 512-element chunk per wave at a time),
 // what is left over, and bfloat16 sources, group-wise.
 template <int KIND, bool AS_BF16>
-__device__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
+__device__ __forceinline__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
   const InvScale inv = inv_scale(j.scale, j.scale_dev, j.kind);
   const uint64_t ctr = first_block(j.counter_offset, j.counter_dev);
   const uint32_t k0 = (uint32_t)j.seed, k1 = (uint32_t)(j.seed >> 32);
@@ -76,8 +84,8 @@ __device__ void flat_path(const QuantJob& j, uint32_t local, uint32_t nblocks) {
 
 // transposed output (cols x rows), optionally a same-layout output as well (out2): the same
 // codes, or those of a second (integer) quantizer of the same values
-template <int KIND, bool AS_BF16>
-__device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem) {
+template <int KIND, bool AS_BF16, int TR>
+__device__ __forceinline__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem) {
   using elem_t = typename std::conditional<AS_BF16, uint16_t, uint8_t>::type;
   constexpr int ES = sizeof(elem_t);
   constexpr int PITCH = TR + 4 / ES;
@@ -214,6 +222,11 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
       for (int e = 0; e < 8; ++e) tile[(gc * 8 + e) * PITCH + r] = (elem_t)c[e];
     }
   }
+  // The transposed output of a large tensor goes out with streaming stores (it is far bigger than the
+  // caches and the write-through form left the wide gradients at 1 TB/s: 65536 x 5632, 450 -> 355 us);
+  // a small one with write-through stores, which leave it in the last-level cache for the product
+  // that reads it next (GPT-2 sizes: a few us per step).
+  const bool stream_out = (size_t)j.rows * j.cols * ES > STREAM_OUT_BYTES;
   __syncthreads();
 #pragma unroll
   for (int it = 0; it < (TC * TR / 16) / QBLOCK; ++it) {
@@ -225,25 +238,38 @@ __device__ void transpose_path(const QuantJob& j, uint32_t local, uint8_t* smem)
     if (KIND == SRQ_INT4 && !AS_BF16 && j.pack_t) {
       // two values per byte along the transposed row: byte j of 8 = elements j and j + 8 of the 16
       const uint32_t m = 0x0F0F0F0Fu;
-      store_through8(j.out + (((size_t)col * rows + row) >> 1),
-                     u32x2{(src[0] & m) | ((src[2] & m) << 4), (src[1] & m) | ((src[3] & m) << 4)});
+      const u32x2 w = {(src[0] & m) | ((src[2] & m) << 4), (src[1] & m) | ((src[3] & m) << 4)};
+      uint8_t* const dst = j.out + (((size_t)col * rows + row) >> 1);
+      if (stream_out) __builtin_nontemporal_store(w, reinterpret_cast<u32x2*>(dst));
+      else store_through8(dst, w);
       continue;
     }
     elem_t* dst = reinterpret_cast<elem_t*>(j.out) + (size_t)col * rows + row;
 #pragma unroll
-    for (int i = 0; i < ES; ++i)
-      store_through16(reinterpret_cast<u32x4*>(dst) + i, u32x4{src[4 * i], src[4 * i + 1], src[4 * i + 2], src[4 * i + 3]});
+    for (int i = 0; i < ES; ++i) {
+      const u32x4 w = {src[4 * i], src[4 * i + 1], src[4 * i + 2], src[4 * i + 3]};
+      if (stream_out) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(dst) + i);
+      else store_through16(reinterpret_cast<u32x4*>(dst) + i, w);
+    }
   }
 }
 
 template <int KIND, bool AS_BF16>
 __device__ __forceinline__ void run_job(const QuantJob& j, uint32_t local, uint8_t* smem) {
-  if (j.transpose) transpose_path<KIND, AS_BF16>(j, local, smem);
+  if (j.transpose) {
+    if constexpr (AS_BF16) {
+      transpose_path<KIND, true, 128>(j, local, smem);
+    } else {
+      if (tile_rows(false, j.rows, j.cols) == 256) transpose_path<KIND, false, 256>(j, local, smem);
+      else transpose_path<KIND, false, 128>(j, local, smem);
+    }
+  }
   else flat_path<KIND, AS_BF16>(j, local, j.nblocks);
 }
 
 __global__ __launch_bounds__(QBLOCK) void quantize_jobs_kernel(QuantJobs jobs) {
-  __shared__ __attribute__((aligned(16))) uint8_t smem[TC * (TR + 2) * 2];
+  __shared__ __attribute__((aligned(16))) uint8_t smem[TC * (128 + 2) * 2];
+  static_assert(TC * (256 + 4) <= (int)sizeof(smem), "the tile of 256 rows of bytes fits as well");
   int ji = 0;
 #pragma unroll
   for (int i = 1; i < QUANT_JOBS_MAX; ++i)
@@ -290,7 +316,8 @@ hipError_t launch_quantize_jobs(QuantJobs& jobs, hipStream_t stream) {
     QuantJob& j = jobs.job[i];
     size_t nb;
     if (j.transpose) {
-      nb = (size_t)((j.cols + TC - 1) / TC) * ((j.rows + TR - 1) / TR);
+      const size_t tr = tile_rows(j.store == STORE_BF16, j.rows, j.cols);
+      nb = (size_t)((j.cols + TC - 1) / TC) * ((j.rows + tr - 1) / tr);
     } else {
       const size_t groups = (size_t)j.rows * j.cols / 8;
       nb = (groups + FLAT_GROUPS_PER_BLOCK - 1) / FLAT_GROUPS_PER_BLOCK;
