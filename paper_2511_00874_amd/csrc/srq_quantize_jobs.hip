@@ -23,7 +23,7 @@ __host__ __device__ inline int tile_rows(bool as_bf16, uint32_t rows, uint32_t c
   return !as_bf16 && (size_t)((rows + 255u) / 256u) * ((cols + TC - 1) / TC) >= 2048u ? 256 : 128;
 }
 constexpr size_t STREAM_OUT_BYTES = 64u << 20;
-constexpr int BAND_GROUP = 16;          // row bands whose tiles are walked together (tile order)
+constexpr int BAND_GROUP = 32;         // row bands whose tiles are walked together (tile order)
 static_assert(BAND_GROUP % 8 == 0, "neighbouring column tiles of a band on one XCD");
 constexpr int FLAT_GROUPS_PER_BLOCK = QBLOCK * 4;  // sixteen 512-element chunks: four per wave (measured best of 1, 2, 4, 8)
 

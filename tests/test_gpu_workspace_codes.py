@@ -86,8 +86,8 @@ def test_gpt2_fc1_benchmark_formats(kind):
 
 
 def test_many_row_bands_with_a_ragged_last_group():
-    # the transposing quantizer walks its tiles in groups of 16 bands of 128 rows: 37 full bands and
-    # a band of 16 rows make two full groups and one of six bands, the last of them partial
+    # the transposing quantizer walks its tiles in groups of 32 bands of 128 rows: 37 full bands and
+    # a band of 16 rows make one full group and one of six bands, the last of them partial
     say("workspace codes, 4752 rows")
     _run(4752, 144, 208, L.INT8, seed=5, w_bf16=True)
 
