@@ -285,7 +285,9 @@ int sr_linear_bwd_weight(float* dW, const void* dY, int dtypedY, const void* A, 
  * whenever the two products use the same pipeline in both forms of the call (always, except
  * when exactly one of W, A shares the E5M2 format with dY: the stored Q(dY) then has to serve
  * both products as bfloat16, and the E5M2 x E5M2 product differs from the separate call in the
- * order of its binary32 sums).
+ * order of its binary32 sums).  The form in which the workspace holds the quantized operands is
+ * the library's own (a 4-bit Q(dY) of a binary32 dY, for one, is kept two values per byte for the
+ * products that run on 256 x 256 tiles; the results are those of one byte per value bit for bit).
  * workspace: sr_linear_workspace_bytes(SRQ_OP_BWD, M, N, K). */
 int sr_linear_bwd(float* dA, float* dW, const void* dY, int dtypedY, const void* W, int dtypeW,
                   const void* A, int dtypeA, size_t M, size_t N, size_t K, const srq_quant* qdY_bwd,
