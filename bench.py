@@ -28,7 +28,7 @@ GPT2_TOKENS = 8192
 # Bytes moved behind the L2 per launch of the dominant kernel (int8 product, 256 x 256 tiles) on the nine
 # products of the headline workload, slice sums included: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by
 # what the same counters read for a plain copy of known size (profiles/product_int8_llama_hbm_traffic.txt)
-TRAFFIC_I8_PRODUCT_LLAMA = 1392594943
+TRAFFIC_I8_PRODUCT_LLAMA = 1393623303
 TRAFFIC_QUANTIZE_INT8_2P28 = (1024.0 + 256.0) * 2**20
 
 
